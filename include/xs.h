@@ -1,0 +1,213 @@
+/*
+ * xs - fused gradient synchronisation for CrossoverScheduler (arXiv 2103.07974)
+ *      on AMD Instinct MI355X (gfx950).  C99 interface of libxs.so.
+ *
+ * One synchronisation of one training task is
+ *     pack      every worker's per-layer gradient tensors into one fused bucket
+ *               (Section 2.1, tensor fusion; Algorithm 1 "Fuse all gradient into
+ *               one group"),
+ *     reduce    the W workers' buckets in worker order 0..W-1 and average them
+ *               (Algorithm 1 "Receive averaged gradients"),
+ *     update    the parameters with momentum SGD in the same pass
+ *               (Algorithm 1 "Model Update", x <- SGD(x, g)),
+ *     unpack    the updated parameter bucket into the per-layer tensors,
+ * and the scheduler alternates one task's gradient computation with another
+ * task's synchronisation on two HIP streams (Algorithm 1; Section 2.1).
+ *
+ * All W workers' gradients are resident on one GPU (that GPU's share of the
+ * reduction); the library performs no communication.
+ *
+ * General rules
+ *  - Every function returns an xs_status (0 = success, negative = error) and never
+ *    throws or aborts.  Arguments are validated before anything is launched; on
+ *    error nothing has been enqueued.  xs_last_error() gives a thread-local
+ *    description of the last failure in the calling thread.
+ *  - "device" pointers are HIP device addresses; "host" pointers are ordinary
+ *    process memory that is read during the call only.
+ *  - The caller owns every data buffer (tensors, pointer tables, buckets,
+ *    parameters, momentum, flags).  The library owns only what *_create returns.
+ *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *    The four hot calls (xs_fuse_pack, xs_fused_reduce_sgd, xs_fuse_unpack,
+ *    xs_crossover_step) only enqueue work and return; they allocate no memory
+ *    and do not synchronise.  Execution errors surface at the caller's next
+ *    synchronisation.
+ *  - Same inputs give bit-identical outputs on every call.
+ */
+#ifndef XS_H
+#define XS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define XS_MAX_REPLICAS 32   /* largest W accepted by xs_fused_reduce_sgd */
+
+typedef enum {
+    XS_OK = 0,
+    XS_ERR_INVALID_ARG = -1,  /* NULL required pointer, W out of range, bad handle, aliasing */
+    XS_ERR_ALIGNMENT   = -2,  /* a bucket / parameter / momentum pointer is not 16-byte aligned */
+    XS_ERR_SIZE        = -3,  /* offsets not monotone, overlap, sizes inconsistent */
+    XS_ERR_UNSUPPORTED = -4,  /* unknown dtype or option */
+    XS_ERR_HIP         = -5,  /* a HIP runtime call failed; see xs_last_error() */
+    XS_ERR_NOMEM       = -6,  /* host or device allocation failed in a *_create call */
+    XS_ERR_STATE       = -7   /* crossover call out of order (nothing to synchronise) */
+} xs_status;
+
+typedef enum { XS_F32 = 0, XS_F16 = 1 } xs_dtype;   /* gradient element type */
+
+/* Static string for a status code. */
+const char *xs_status_string(int status);
+/* Thread-local detail of the last error in this thread ("" if none). */
+const char *xs_last_error(void);
+
+/* ------------------------------------------------------------------------
+ * Bucket layout (Section 2.1: all tensors of one model form one united tensor).
+ * offsets_out[0] = 0; offsets_out[t+1] = offsets_out[t] + numel[t] rounded up to
+ * a multiple of align_elems; offsets_out[n_tensors] is the bucket length in
+ * elements.  align_elems = 1 is plain concatenation.  Host pointers.
+ * Errors: NULL pointer (n_tensors > 0), align_elems == 0.
+ */
+int xs_bucket_layout(const uint64_t *numel, uint32_t n_tensors, uint64_t align_elems,
+                     uint64_t *offsets_out /* n_tensors + 1 */);
+
+/* ------------------------------------------------------------------------
+ * Plan: device-resident description of one tensor list's place in its bucket.
+ * numel[t], offsets[t] (host, read during the call): tensor t occupies bucket
+ * elements [offsets[t], offsets[t]+numel[t]); offsets has n_tensors+1 entries,
+ * offsets[0] == 0, offsets[t]+numel[t] <= offsets[t+1], and offsets[n_tensors]
+ * is the bucket length.  Elements between a tensor's end and the next offset
+ * are padding.  dtype is the element type moved by pack/unpack with this plan.
+ * xs_plan_create allocates small device tables and synchronises once.
+ * n_tensors == 0 and numel[t] == 0 are valid.
+ */
+typedef struct xs_plan xs_plan;
+int xs_plan_create(const uint64_t *numel, const uint64_t *offsets, uint32_t n_tensors,
+                   int dtype, xs_plan **out);
+int xs_plan_destroy(xs_plan *plan);                 /* NULL is accepted */
+uint64_t xs_plan_bucket_elems(const xs_plan *plan); /* offsets[n_tensors]; 0 for NULL */
+uint32_t xs_plan_n_tensors(const xs_plan *plan);
+
+/* ------------------------------------------------------------------------
+ * Pack (Algorithm 1, "Fuse all gradient into one group"): bit copy of every
+ * tensor into the bucket at its offset; padding elements are written as +0.
+ *   tensor_ptrs  device array of n_tensors device pointers (element-aligned;
+ *                any further alignment is handled), owned by the caller and
+ *                read by the kernel when it runs
+ *   bucket       device, 16-byte aligned, xs_plan_bucket_elems() elements
+ *   found_inf    device int32, may be NULL; set to 1 by the kernel if any
+ *                copied element is +-inf or NaN (never cleared by the library)
+ * The bucket must not overlap any tensor.
+ */
+int xs_fuse_pack(const xs_plan *plan, const void *const *tensor_ptrs, void *bucket,
+                 int32_t *found_inf, void *hip_stream);
+
+/* Unpack: inverse of pack.  Copies each tensor's range of the bucket to
+ * tensor_ptrs[t]; padding is ignored.  Same pointer conventions as pack. */
+int xs_fuse_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,
+                   void *hip_stream);
+
+/* ------------------------------------------------------------------------
+ * Fused reduce + average + momentum-SGD (Algorithm 1, "Receive averaged
+ * gradients" and "Model Update"), one pass over memory.  For every j < n_elems
+ *     s = g_0[j] + g_1[j] + ... + g_{W-1}[j]     (left to right, fp32;
+ *                                                 fp16 gradients widened first)
+ *     g = s * (inv_loss_scale * (1/W))
+ *     d = g + weight_decay * x[j];  v[j] = momentum * v[j] + d;  x[j] -= lr * v[j]
+ * every operation rounded to fp32 separately (no fused multiply-add).
+ *
+ *   replica_buckets  host array of W device pointers, each 16-byte aligned and
+ *                    holding n_elems elements of grad_dtype; replicas may alias
+ *                    one another but not the parameter or momentum buffers
+ *   params, momentum device fp32, 16-byte aligned, n_elems each
+ *   params_out, momentum_out   both NULL: update in place.  Both non-NULL
+ *                    (16-byte aligned, n_elems, overlapping nothing else):
+ *                    results are written there and the inputs are left intact.
+ *   found_inf        device int32, may be NULL.  If non-NULL and nonzero when the
+ *                    kernel starts, the kernel writes nothing (step skipped).
+ *                    In the out-of-place form the kernel additionally sets it to
+ *                    1 when any gradient element in [0, n_elems) is +-inf or
+ *                    NaN; the caller then discards the outputs.  The in-place
+ *                    form relies on xs_fuse_pack having raised the flag on the
+ *                    same stream, since an in-place pass cannot be undone.
+ * W in [1, XS_MAX_REPLICAS].  n_elems == 0 is a no-op.
+ */
+typedef struct {
+    float lr;
+    float momentum;
+    float weight_decay;
+    float inv_loss_scale;   /* 1.0f when no loss scaling is used */
+} xs_sgd_hparams;
+
+int xs_fused_reduce_sgd(const void *const *replica_buckets, uint32_t W, int grad_dtype,
+                        uint64_t n_elems, float *params, float *momentum,
+                        float *params_out, float *momentum_out,
+                        const xs_sgd_hparams *hp, int32_t *found_inf, void *hip_stream);
+
+/* ------------------------------------------------------------------------
+ * Training task ("distributed task i" of Algorithm 1) as seen by the scheduler.
+ * All pointers in the descriptor are copied or referenced as stated and must
+ * stay valid until xs_app_destroy.
+ */
+typedef void (*xs_compute_fn)(void *user_ctx, void *hip_stream);
+/* Enqueues the task's gradient computation (forward + backward) on hip_stream and
+ * returns without blocking; it must leave worker w's gradients in the tensors
+ * that grad_tensor_ptrs[w] points to. */
+
+typedef struct {
+    const xs_plan *gradient_plan;            /* layout in the gradient dtype          */
+    const xs_plan *parameter_plan;           /* same layout, dtype XS_F32             */
+    uint32_t W;                              /* workers resident on this GPU          */
+    const void *const *const *grad_tensor_ptrs; /* host array of W device pointer tables  */
+    void *const *replica_buckets;            /* host array of W device buckets        */
+    float *params;                           /* device, bucket layout, fp32           */
+    float *momentum;                         /* device, bucket layout, fp32           */
+    void *const *param_tensor_ptrs;          /* device pointer table of parameter views */
+    xs_sgd_hparams hp;
+    int32_t *found_inf;                      /* device, may be NULL                   */
+    xs_compute_fn compute;                   /* may be NULL (no compute enqueued)     */
+    void *compute_ctx;
+} xs_app_desc;
+
+typedef struct xs_app xs_app;
+int xs_app_create(const xs_app_desc *desc, xs_app **out);   /* creates two HIP events */
+int xs_app_destroy(xs_app *app);                            /* NULL is accepted */
+
+/* The whole synchronisation of one task on one stream: W packs, fused
+ * reduce + SGD in place, unpack of the parameters.  Enqueue only. */
+int xs_app_sync(xs_app *app, void *hip_stream);
+
+/* One inner step of Algorithm 1 for two tasks: compute_app's gradient computation
+ * is enqueued on compute_stream (after its own previous synchronisation, so that
+ * it sees updated parameters) while sync_app's synchronisation is enqueued on
+ * sync_stream (after the computation that produced its gradients).  sync_app ==
+ * NULL is the first-iteration bypass of Section 2.2.  Returns XS_ERR_STATE if
+ * sync_app has no gradients outstanding.  Enqueue only; no host synchronisation.
+ */
+int xs_crossover_step(xs_app *compute_app, xs_app *sync_app,
+                      void *compute_stream, void *sync_stream);
+
+/* The additional synchronisation phase after the last iteration (Section 2.2):
+ * synchronises app's outstanding gradients on sync_stream.  XS_ERR_STATE if none. */
+int xs_crossover_drain(xs_app *app, void *sync_stream);
+
+/* Makes hip_stream wait for app's last enqueued synchronisation (no-op if none). */
+int xs_app_wait_sync(xs_app *app, void *hip_stream);
+
+/* ------------------------------------------------------------------------
+ * Launch tuning (process-wide; defaults are the measured best for MI355X).
+ * key: 0 = reduce kernel workgroups per compute unit (0 = one vector per thread,
+ *          no grid-stride loop),
+ *      1 = pack/unpack workgroups per compute unit,
+ *      2 = non-temporal loads of gradient replicas (0/1),
+ *      3 = non-temporal stores of parameters and momentum (0/1).
+ * Returns XS_ERR_INVALID_ARG for an unknown key or out-of-range value.
+ */
+int xs_tuning_set(int key, int value);
+int xs_tuning_get(int key, int *value_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XS_H */

@@ -1,0 +1,287 @@
+// Host side of libxs.so: status strings, error text, bucket layout, plans, tuning,
+// and the argument validation of the three data-moving entry points.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "xs_internal.h"
+
+namespace xs {
+
+static thread_local char t_error[512] = "";
+
+int fail(int status, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(t_error, sizeof t_error, fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+int fail_hip(hipError_t e, const char *what)
+{
+    snprintf(t_error, sizeof t_error, "%s: %s", what, hipGetErrorString(e));
+    return XS_ERR_HIP;
+}
+
+void clear_error() { t_error[0] = '\0'; }
+
+int compute_units()
+{
+    static int cached = 0;
+    if (cached > 0) return cached;
+    int dev = 0, cus = 0;
+    XS_HIP_TRY(hipGetDevice(&dev));
+    XS_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if (cus <= 0) return fail(XS_ERR_HIP, "device reports %d compute units", cus);
+    cached = cus;
+    return cus;
+}
+
+Tuning g_tuning = {/*reduce_wg_per_cu*/ 8, /*copy_wg_per_cu*/ 8, /*nt_loads*/ 1, /*nt_stores*/ 0};
+
+}  // namespace xs
+
+using namespace xs;
+
+extern "C" const char *xs_status_string(int status)
+{
+    switch (status) {
+    case XS_OK: return "XS_OK";
+    case XS_ERR_INVALID_ARG: return "XS_ERR_INVALID_ARG";
+    case XS_ERR_ALIGNMENT: return "XS_ERR_ALIGNMENT";
+    case XS_ERR_SIZE: return "XS_ERR_SIZE";
+    case XS_ERR_UNSUPPORTED: return "XS_ERR_UNSUPPORTED";
+    case XS_ERR_HIP: return "XS_ERR_HIP";
+    case XS_ERR_NOMEM: return "XS_ERR_NOMEM";
+    case XS_ERR_STATE: return "XS_ERR_STATE";
+    default: return "XS_ERR_UNKNOWN";
+    }
+}
+
+extern "C" const char *xs_last_error(void) { return t_error; }
+
+extern "C" int xs_tuning_set(int key, int value)
+{
+    switch (key) {
+    case 0: if (value < 0 || value > 64) break; g_tuning.reduce_wg_per_cu = value; return XS_OK;
+    case 1: if (value < 1 || value > 64) break; g_tuning.copy_wg_per_cu = value; return XS_OK;
+    case 2: if (value < 0 || value > 1) break; g_tuning.nt_loads = value; return XS_OK;
+    case 3: if (value < 0 || value > 1) break; g_tuning.nt_stores = value; return XS_OK;
+    default: return fail(XS_ERR_INVALID_ARG, "xs_tuning_set: unknown key %d", key);
+    }
+    return fail(XS_ERR_INVALID_ARG, "xs_tuning_set: value %d out of range for key %d", value, key);
+}
+
+extern "C" int xs_tuning_get(int key, int *value_out)
+{
+    if (!value_out) return fail(XS_ERR_INVALID_ARG, "xs_tuning_get: value_out is NULL");
+    switch (key) {
+    case 0: *value_out = g_tuning.reduce_wg_per_cu; return XS_OK;
+    case 1: *value_out = g_tuning.copy_wg_per_cu; return XS_OK;
+    case 2: *value_out = g_tuning.nt_loads; return XS_OK;
+    case 3: *value_out = g_tuning.nt_stores; return XS_OK;
+    default: return fail(XS_ERR_INVALID_ARG, "xs_tuning_get: unknown key %d", key);
+    }
+}
+
+// Section 2.1, tensor fusion: tensors laid end to end, each start rounded up.
+extern "C" int xs_bucket_layout(const uint64_t *numel, uint32_t n_tensors, uint64_t align_elems,
+                                uint64_t *offsets_out)
+{
+    if (!offsets_out) return fail(XS_ERR_INVALID_ARG, "xs_bucket_layout: offsets_out is NULL");
+    if (n_tensors > 0 && !numel) return fail(XS_ERR_INVALID_ARG, "xs_bucket_layout: numel is NULL");
+    if (align_elems == 0) return fail(XS_ERR_INVALID_ARG, "xs_bucket_layout: align_elems is 0");
+    uint64_t pos = 0;
+    offsets_out[0] = 0;
+    for (uint32_t t = 0; t < n_tensors; ++t) {
+        if (numel[t] > UINT64_MAX - pos - align_elems)
+            return fail(XS_ERR_SIZE, "xs_bucket_layout: bucket length overflows 64 bits");
+        pos += numel[t];
+        pos = (pos + align_elems - 1) / align_elems * align_elems;
+        offsets_out[t + 1] = pos;
+    }
+    return XS_OK;
+}
+
+static int elem_size_of(int dtype)
+{
+    switch (dtype) {
+    case XS_F32: return 4;
+    case XS_F16: return 2;
+    default: return 0;
+    }
+}
+
+extern "C" int xs_plan_create(const uint64_t *numel, const uint64_t *offsets, uint32_t n_tensors,
+                              int dtype, xs_plan **out)
+{
+    if (!out) return fail(XS_ERR_INVALID_ARG, "xs_plan_create: out is NULL");
+    *out = nullptr;
+    if (!offsets || (n_tensors > 0 && !numel))
+        return fail(XS_ERR_INVALID_ARG, "xs_plan_create: numel/offsets is NULL");
+    const int es = elem_size_of(dtype);
+    if (es == 0) return fail(XS_ERR_UNSUPPORTED, "xs_plan_create: unknown dtype %d", dtype);
+    if (offsets[0] != 0) return fail(XS_ERR_SIZE, "xs_plan_create: offsets[0] must be 0");
+    if (n_tensors >= UINT32_MAX - 1) return fail(XS_ERR_SIZE, "xs_plan_create: too many tensors");
+
+    std::vector<uint32_t> prefix(n_tensors + 1, 0);
+    uint64_t chunks = 0;
+    for (uint32_t t = 0; t < n_tensors; ++t) {
+        if (offsets[t + 1] < offsets[t] || numel[t] > offsets[t + 1] - offsets[t])
+            return fail(XS_ERR_SIZE,
+                        "xs_plan_create: tensor %u (numel %llu at offset %llu) overruns the next offset %llu",
+                        t, (unsigned long long)numel[t], (unsigned long long)offsets[t],
+                        (unsigned long long)offsets[t + 1]);
+        if (offsets[t + 1] > (UINT64_MAX >> 4))
+            return fail(XS_ERR_SIZE, "xs_plan_create: bucket too large");
+        const uint64_t seg_bytes = (offsets[t + 1] - offsets[t]) * (uint64_t)es;
+        prefix[t] = (uint32_t)chunks;
+        chunks += (seg_bytes + kChunkBytes - 1) / kChunkBytes;
+        if (chunks > 0x7fffffffull) return fail(XS_ERR_SIZE, "xs_plan_create: bucket too large");
+    }
+    prefix[n_tensors] = (uint32_t)chunks;
+
+    xs_plan *p = new (std::nothrow) xs_plan();
+    if (!p) return fail(XS_ERR_NOMEM, "xs_plan_create: host allocation failed");
+    p->magic = XS_PLAN_MAGIC;
+    p->n_tensors = n_tensors;
+    p->dtype = dtype;
+    p->elem_size = (uint32_t)es;
+    p->bucket_elems = offsets[n_tensors];
+    p->n_chunks = (uint32_t)chunks;
+    p->dev_blob = nullptr;
+
+    // one device blob: offsets | numel | chunk_prefix
+    const size_t off_bytes = (size_t)(n_tensors + 1) * 8;
+    const size_t num_bytes = (size_t)n_tensors * 8;
+    const size_t pre_bytes = (size_t)(n_tensors + 1) * 4;
+    std::vector<unsigned char> host(off_bytes + num_bytes + pre_bytes);
+    memcpy(host.data(), offsets, off_bytes);
+    if (n_tensors) memcpy(host.data() + off_bytes, numel, num_bytes);
+    memcpy(host.data() + off_bytes + num_bytes, prefix.data(), pre_bytes);
+    hipError_t e = hipMalloc(&p->dev_blob, host.size());
+    if (e != hipSuccess) {
+        delete p;
+        fail_hip(e, "hipMalloc(plan tables)");
+        return e == hipErrorOutOfMemory ? XS_ERR_NOMEM : XS_ERR_HIP;
+    }
+    e = hipMemcpy(p->dev_blob, host.data(), host.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(p->dev_blob);
+        delete p;
+        return fail_hip(e, "hipMemcpy(plan tables)");
+    }
+    unsigned char *d = (unsigned char *)p->dev_blob;
+    p->tables.offsets = (const uint64_t *)d;
+    p->tables.numel = (const uint64_t *)(d + off_bytes);
+    p->tables.chunk_prefix = (const uint32_t *)(d + off_bytes + num_bytes);
+    *out = p;
+    return XS_OK;
+}
+
+extern "C" int xs_plan_destroy(xs_plan *plan)
+{
+    if (!plan) return XS_OK;
+    if (plan->magic != XS_PLAN_MAGIC) return fail(XS_ERR_INVALID_ARG, "xs_plan_destroy: not a plan");
+    plan->magic = 0;
+    hipError_t e = plan->dev_blob ? hipFree(plan->dev_blob) : hipSuccess;
+    delete plan;
+    if (e != hipSuccess) return fail_hip(e, "hipFree(plan tables)");
+    return XS_OK;
+}
+
+extern "C" uint64_t xs_plan_bucket_elems(const xs_plan *plan)
+{
+    return (plan && plan->magic == XS_PLAN_MAGIC) ? plan->bucket_elems : 0;
+}
+
+extern "C" uint32_t xs_plan_n_tensors(const xs_plan *plan)
+{
+    return (plan && plan->magic == XS_PLAN_MAGIC) ? plan->n_tensors : 0;
+}
+
+// ---- Algorithm 1, "Fuse all gradient into one group" -----------------------------
+extern "C" int xs_fuse_pack(const xs_plan *plan, const void *const *tensor_ptrs, void *bucket,
+                            int32_t *found_inf, void *hip_stream)
+{
+    if (!plan || plan->magic != XS_PLAN_MAGIC)
+        return fail(XS_ERR_INVALID_ARG, "xs_fuse_pack: plan is NULL or not a plan");
+    if (plan->n_chunks == 0) return XS_OK;
+    if (!bucket) return fail(XS_ERR_INVALID_ARG, "xs_fuse_pack: bucket is NULL");
+    if (!tensor_ptrs) return fail(XS_ERR_INVALID_ARG, "xs_fuse_pack: tensor_ptrs is NULL");
+    if (!aligned16(bucket)) return fail(XS_ERR_ALIGNMENT, "xs_fuse_pack: bucket is not 16-byte aligned");
+    if (found_inf && ((uintptr_t)found_inf & 3u))
+        return fail(XS_ERR_ALIGNMENT, "xs_fuse_pack: found_inf is not 4-byte aligned");
+    return launch_pack(plan, tensor_ptrs, bucket, found_inf, (hipStream_t)hip_stream);
+}
+
+extern "C" int xs_fuse_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,
+                              void *hip_stream)
+{
+    if (!plan || plan->magic != XS_PLAN_MAGIC)
+        return fail(XS_ERR_INVALID_ARG, "xs_fuse_unpack: plan is NULL or not a plan");
+    if (plan->n_chunks == 0) return XS_OK;
+    if (!bucket) return fail(XS_ERR_INVALID_ARG, "xs_fuse_unpack: bucket is NULL");
+    if (!tensor_ptrs) return fail(XS_ERR_INVALID_ARG, "xs_fuse_unpack: tensor_ptrs is NULL");
+    if (!aligned16(bucket)) return fail(XS_ERR_ALIGNMENT, "xs_fuse_unpack: bucket is not 16-byte aligned");
+    return launch_unpack(plan, bucket, tensor_ptrs, (hipStream_t)hip_stream);
+}
+
+// ---- Algorithm 1, "Receive averaged gradients" + "Model Update" ----------------------
+static bool overlaps(const void *a, uint64_t a_bytes, const void *b, uint64_t b_bytes)
+{
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + b_bytes && b0 < a0 + a_bytes;
+}
+
+extern "C" int xs_fused_reduce_sgd(const void *const *replica_buckets, uint32_t W, int grad_dtype,
+                                   uint64_t n_elems, float *params, float *momentum,
+                                   float *params_out, float *momentum_out,
+                                   const xs_sgd_hparams *hp, int32_t *found_inf, void *hip_stream)
+{
+    const int es = elem_size_of(grad_dtype);
+    if (es == 0) return fail(XS_ERR_UNSUPPORTED, "xs_fused_reduce_sgd: unknown grad_dtype %d", grad_dtype);
+    if (W == 0 || W > XS_MAX_REPLICAS)
+        return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd: W = %u outside [1, %d]", W, XS_MAX_REPLICAS);
+    if (!hp) return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd: hp is NULL");
+    if ((params_out == nullptr) != (momentum_out == nullptr))
+        return fail(XS_ERR_INVALID_ARG,
+                    "xs_fused_reduce_sgd: params_out and momentum_out must both be NULL or both be given");
+    if (n_elems == 0) return XS_OK;
+    if (n_elems > (UINT64_MAX >> 4)) return fail(XS_ERR_SIZE, "xs_fused_reduce_sgd: n_elems too large");
+    if (!replica_buckets || !params || !momentum)
+        return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd: replica_buckets/params/momentum is NULL");
+    const bool out_of_place = params_out != nullptr;
+    if (!aligned16(params) || !aligned16(momentum) ||
+        (out_of_place && (!aligned16(params_out) || !aligned16(momentum_out))))
+        return fail(XS_ERR_ALIGNMENT, "xs_fused_reduce_sgd: params/momentum pointers must be 16-byte aligned");
+    if (found_inf && ((uintptr_t)found_inf & 3u))
+        return fail(XS_ERR_ALIGNMENT, "xs_fused_reduce_sgd: found_inf is not 4-byte aligned");
+    const uint64_t sbytes = n_elems * 4, gbytes = n_elems * (uint64_t)es;
+    const void *state[4] = {params, momentum, params_out, momentum_out};
+    const int n_state = out_of_place ? 4 : 2;
+    for (int a = 0; a < n_state; ++a)
+        for (int b = a + 1; b < n_state; ++b)
+            if (overlaps(state[a], sbytes, state[b], sbytes))
+                return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd: params/momentum buffers overlap");
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!replica_buckets[w])
+            return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd: replica_buckets[%u] is NULL", w);
+        if (!aligned16(replica_buckets[w]))
+            return fail(XS_ERR_ALIGNMENT, "xs_fused_reduce_sgd: replica_buckets[%u] is not 16-byte aligned", w);
+        for (int a = 0; a < n_state; ++a)
+            if (overlaps(replica_buckets[w], gbytes, state[a], sbytes))
+                return fail(XS_ERR_INVALID_ARG,
+                            "xs_fused_reduce_sgd: replica_buckets[%u] overlaps a parameter/momentum buffer", w);
+    }
+    return launch_reduce_sgd(replica_buckets, W, grad_dtype, n_elems, params, momentum,
+                             out_of_place ? params_out : params,
+                             out_of_place ? momentum_out : momentum, *hp, found_inf,
+                             /*detect=*/out_of_place && found_inf != nullptr,
+                             (hipStream_t)hip_stream);
+}

@@ -1,0 +1,198 @@
+// Pack / unpack between a list of per-layer tensors and one fused bucket on gfx950
+// (arXiv 2103.07974, Section 2.1 tensor fusion; Algorithm 1 "Fuse all gradient into
+// one group" and its inverse).
+//
+// One launch moves the whole list, however many small tensors it has.  The bucket
+// is cut into chunks of kChunkBytes of one tensor's segment (tensor + trailing
+// padding); a persistent grid of workgroups walks the chunk ids in stride.  Each
+// workgroup copies the per-tensor chunk-count prefix table into LDS once and finds
+// the tensor of every chunk by binary search there (the table is uniform across
+// the workgroup, so the LDS reads are broadcasts).  Inside a chunk each lane moves
+// 16-byte vectors: the bucket side is always 16-byte aligned, the tensor side is
+// accessed with element-aligned 16-byte loads/stores (gfx950 global memory
+// instructions do not need natural alignment), so tight layouts and odd tensor
+// addresses stay on the vector path.  Only the partial vectors at a chunk's two
+// ends and at the tensor/padding boundary go element by element.
+//
+// HBM-bound: 2*s bytes per element (read once, written once); no arithmetic
+// except the exponent test that raises the overflow flag while packing.
+#include "xs_internal.h"
+
+namespace xs {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// tensor addresses arrive as integers; say that they are global memory so that the
+// copies compile to global_* rather than flat_* instructions
+typedef __attribute__((address_space(1))) unsigned char gbyte;
+
+template <int ALIGN>
+struct __attribute__((packed, aligned(ALIGN))) LooseVec {
+    u32x4 v;
+};
+
+constexpr int kTrips = (kChunkBytes / 16 + 1 + kCopyThreads - 1) / kCopyThreads;   // 5
+
+// first index in table[0..count) whose value is > key, minus one
+template <typename Table>
+__device__ __forceinline__ uint32_t find_tensor(Table table, uint32_t count, uint32_t key)
+{
+    uint32_t lo = 0, hi = count;          // invariant: table[lo-1] <= key < table[hi]
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (table[mid] <= key) lo = mid + 1;
+        else hi = mid;
+    }
+    return lo - 1;
+}
+
+template <int ES>
+__device__ __forceinline__ bool nonfinite_word(uint32_t w)
+{
+    if constexpr (ES == 4) return (w & 0x7f800000u) == 0x7f800000u;
+    else return (((w & 0x7c007c00u) + 0x04000400u) & 0x80008000u) != 0u;
+}
+
+template <int ES>
+__device__ __forceinline__ bool nonfinite_elem(uint32_t bits)
+{
+    if constexpr (ES == 4) return (bits & 0x7f800000u) == 0x7f800000u;
+    else return (bits & 0x7c00u) == 0x7c00u;
+}
+
+template <int ES>
+struct Elem;
+template <>
+struct Elem<4> { typedef uint32_t type; };
+template <>
+struct Elem<2> { typedef uint16_t type; };
+
+// UNPACK = false: tensors -> bucket (padding zero-filled, optional overflow flag)
+// UNPACK = true : bucket -> tensors (padding skipped)
+template <bool UNPACK, bool DETECT, int ES, bool LDS_TABLE>
+__global__ __launch_bounds__(kCopyThreads) void copy_kernel(
+    PlanTables tb, uint32_t n_tensors, uint32_t n_chunks, const uintptr_t *tensor_ptrs,
+    unsigned char *bucket, int32_t *found_inf)
+{
+    typedef typename Elem<ES>::type elem_t;
+    typedef __attribute__((address_space(1))) elem_t gelem;
+    extern __shared__ uint32_t s_prefix[];
+    if constexpr (LDS_TABLE) {
+        for (uint32_t i = threadIdx.x; i <= n_tensors; i += kCopyThreads) s_prefix[i] = tb.chunk_prefix[i];
+        __syncthreads();
+    }
+    bool bad = false;
+
+    for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        uint32_t t, first_chunk;
+        if constexpr (LDS_TABLE) {
+            t = find_tensor(s_prefix, n_tensors + 1, c);
+            t = (uint32_t)__builtin_amdgcn_readfirstlane((int)t);
+            first_chunk = s_prefix[t];
+        } else {
+            t = find_tensor(tb.chunk_prefix, n_tensors + 1, c);
+            t = (uint32_t)__builtin_amdgcn_readfirstlane((int)t);
+            first_chunk = tb.chunk_prefix[t];
+        }
+        const uint64_t seg_begin = tb.offsets[t] * ES;
+        const uint64_t seg_bytes = tb.offsets[t + 1] * ES - seg_begin;
+        const uint64_t val_bytes = tb.numel[t] * ES;
+        const uint64_t k0 = (uint64_t)(c - first_chunk) * kChunkBytes;
+        const uint64_t left = seg_bytes - k0;
+        const int32_t len = (int32_t)(left < kChunkBytes ? left : kChunkBytes);       // bytes in this chunk
+        const int32_t vlen = val_bytes <= k0 ? 0
+                             : (int32_t)((val_bytes - k0) < (uint64_t)len ? (val_bytes - k0) : (uint64_t)len);
+        gbyte *b = (gbyte *)bucket + seg_begin + k0;                // bucket side of the chunk
+        gbyte *q = (gbyte *)tensor_ptrs[t] + k0;                    // tensor side of the chunk
+        const int32_t skew = (int32_t)((uintptr_t)b & 15u);         // bucket vectors start at b - skew
+        const int32_t nvec = (skew + len + 15) >> 4;
+
+        u32x4 r[kTrips];
+        bool fast[kTrips];
+#pragma unroll
+        for (int u = 0; u < kTrips; ++u) {
+            const int32_t j = (int32_t)threadIdx.x + u * (int32_t)kCopyThreads;
+            const int32_t lo = j * 16 - skew;                       // byte offset inside the chunk
+            fast[u] = j < nvec && lo >= 0 && lo + 16 <= vlen;
+            if (fast[u]) {
+                if constexpr (UNPACK) r[u] = *(const __attribute__((address_space(1))) u32x4 *)(b + lo);
+                else r[u] = ((const __attribute__((address_space(1))) LooseVec<ES> *)(q + lo))->v;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kTrips; ++u) {
+            const int32_t j = (int32_t)threadIdx.x + u * (int32_t)kCopyThreads;
+            const int32_t lo = j * 16 - skew;
+            if (fast[u]) {
+                if constexpr (UNPACK) ((__attribute__((address_space(1))) LooseVec<ES> *)(q + lo))->v = r[u];
+                else {
+                    *(__attribute__((address_space(1))) u32x4 *)(b + lo) = r[u];
+                    if constexpr (DETECT)
+                        bad = bad || nonfinite_word<ES>(r[u][0]) || nonfinite_word<ES>(r[u][1]) ||
+                              nonfinite_word<ES>(r[u][2]) || nonfinite_word<ES>(r[u][3]);
+                }
+            } else if (j < nvec) {
+                const int32_t e0 = lo < 0 ? 0 : lo;
+                const int32_t e1 = lo + 16 < len ? lo + 16 : len;
+                for (int32_t e = e0; e < e1; e += ES) {
+                    if (e < vlen) {
+                        if constexpr (UNPACK) *(gelem *)(q + e) = *(const gelem *)(b + e);
+                        else {
+                            const elem_t bits = *(const gelem *)(q + e);
+                            *(gelem *)(b + e) = bits;
+                            if constexpr (DETECT) bad |= nonfinite_elem<ES>(bits);
+                        }
+                    } else if constexpr (!UNPACK) {
+                        *(gelem *)(b + e) = (elem_t)0;
+                    }
+                }
+            }
+        }
+    }
+
+    if constexpr (DETECT) {
+        if (__builtin_amdgcn_ballot_w64(bad) != 0ull && (threadIdx.x & 63u) == 0u)
+            atomicOr(found_inf, 1);
+    }
+}
+
+template <bool UNPACK, bool DETECT, int ES>
+static int launch_copy(const xs_plan *plan, const void *tensor_ptrs, void *bucket,
+                       int32_t *found_inf, hipStream_t stream)
+{
+    const int cus = compute_units();
+    if (cus < 0) return cus;
+    uint32_t blocks = (uint32_t)cus * (uint32_t)g_tuning.copy_wg_per_cu;
+    if (blocks > plan->n_chunks) blocks = plan->n_chunks;
+    const bool lds = plan->n_tensors + 1 <= kLdsPrefixCap;
+    const size_t lds_bytes = lds ? (size_t)(plan->n_tensors + 1) * 4 : 0;
+    if (lds)
+        hipLaunchKernelGGL((copy_kernel<UNPACK, DETECT, ES, true>), dim3(blocks), dim3(kCopyThreads),
+                           lds_bytes, stream, plan->tables, plan->n_tensors, plan->n_chunks,
+                           (const uintptr_t *)tensor_ptrs, (unsigned char *)bucket, found_inf);
+    else
+        hipLaunchKernelGGL((copy_kernel<UNPACK, DETECT, ES, false>), dim3(blocks), dim3(kCopyThreads),
+                           0, stream, plan->tables, plan->n_tensors, plan->n_chunks,
+                           (const uintptr_t *)tensor_ptrs, (unsigned char *)bucket, found_inf);
+    XS_HIP_TRY(hipGetLastError());
+    return XS_OK;
+}
+
+int launch_pack(const xs_plan *plan, const void *const *tensor_ptrs, void *bucket,
+                int32_t *found_inf, hipStream_t stream)
+{
+    if (plan->elem_size == 4)
+        return found_inf ? launch_copy<false, true, 4>(plan, tensor_ptrs, bucket, found_inf, stream)
+                         : launch_copy<false, false, 4>(plan, tensor_ptrs, bucket, nullptr, stream);
+    return found_inf ? launch_copy<false, true, 2>(plan, tensor_ptrs, bucket, found_inf, stream)
+                     : launch_copy<false, false, 2>(plan, tensor_ptrs, bucket, nullptr, stream);
+}
+
+int launch_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,
+                  hipStream_t stream)
+{
+    if (plan->elem_size == 4)
+        return launch_copy<true, false, 4>(plan, tensor_ptrs, const_cast<void *>(bucket), nullptr, stream);
+    return launch_copy<true, false, 2>(plan, tensor_ptrs, const_cast<void *>(bucket), nullptr, stream);
+}
+
+}  // namespace xs

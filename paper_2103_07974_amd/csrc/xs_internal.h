@@ -1,0 +1,77 @@
+// Internal declarations shared by the translation units of libxs.so (host side).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "xs.h"
+
+namespace xs {
+
+// ---- error reporting -------------------------------------------------------
+int fail(int status, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+int fail_hip(hipError_t e, const char *what);
+void clear_error();
+
+#define XS_HIP_TRY(expr)                                                  \
+    do {                                                                  \
+        hipError_t _e = (expr);                                           \
+        if (_e != hipSuccess) return ::xs::fail_hip(_e, #expr);           \
+    } while (0)
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ---- device facts (queried once per process for the current device) -----------
+int compute_units();   // > 0, or a negative xs_status
+
+// ---- tuning ---------------------------------------------------------------------
+struct Tuning {
+    int reduce_wg_per_cu;   // 0: one vector per thread, no loop
+    int copy_wg_per_cu;
+    int nt_loads;
+    int nt_stores;
+};
+extern Tuning g_tuning;
+
+// ---- plan -------------------------------------------------------------------------
+// Copy work is cut into chunks of kChunkBytes of one tensor's bucket segment
+// (tensor plus trailing padding).  chunk_prefix[t] = number of chunks that belong
+// to tensors before t; a workgroup finds the tensor of a chunk by binary search
+// in a copy of this table held in LDS.
+constexpr uint32_t kChunkBytes = 16384;
+constexpr uint32_t kCopyThreads = 256;
+constexpr uint32_t kLdsPrefixCap = 8192;   // table entries that fit the LDS copy
+
+struct PlanTables {            // device pointers
+    const uint64_t *offsets;   // n_tensors + 1
+    const uint64_t *numel;     // n_tensors
+    const uint32_t *chunk_prefix;  // n_tensors + 1
+};
+
+}  // namespace xs
+
+struct xs_plan {
+    uint32_t magic;
+    uint32_t n_tensors;
+    int dtype;
+    uint32_t elem_size;
+    uint64_t bucket_elems;
+    uint32_t n_chunks;
+    void *dev_blob;            // one allocation holding the three tables
+    xs::PlanTables tables;
+};
+
+constexpr uint32_t XS_PLAN_MAGIC = 0x78735031u;  // "xsP1"
+constexpr uint32_t XS_APP_MAGIC = 0x78734131u;   // "xsA1"
+
+namespace xs {
+// launchers implemented next to their kernels
+int launch_pack(const xs_plan *plan, const void *const *tensor_ptrs, void *bucket,
+                int32_t *found_inf, hipStream_t stream);
+int launch_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,
+                  hipStream_t stream);
+int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64_t n,
+                      const float *x_in, const float *v_in, float *x_out, float *v_out,
+                      const xs_sgd_hparams &hp, int32_t *found_inf, bool detect,
+                      hipStream_t stream);
+}  // namespace xs

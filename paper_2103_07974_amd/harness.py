@@ -1,0 +1,84 @@
+"""Device-side set-up of one training task's synchronisation state for tests and the
+benchmark: allocation and pointer tables only, no arithmetic of the method."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Callable, List, Optional
+
+import torch
+
+from . import workloads as wl
+from . import xs
+
+DEFAULT_ALIGN = 64   # elements; keeps every tensor's bucket segment 128/256-byte aligned
+
+
+@dataclass
+class TaskState:
+    workload: wl.Workload
+    align: int
+    offsets: List[int]
+    gplan: xs.Plan
+    pplan: xs.Plan
+    grads: List[List[torch.Tensor]]          # [W][T] per-tensor gradients (device)
+    grad_tables: List[torch.Tensor]          # [W] device pointer tables
+    buckets: List[torch.Tensor]              # [W] fused gradient buckets
+    param_tensors: List[torch.Tensor]        # [T] per-tensor parameter views (device)
+    param_table: torch.Tensor
+    params: torch.Tensor                     # fp32 bucket
+    momentum: torch.Tensor                   # fp32 bucket
+    found_inf: torch.Tensor                  # int32[1]
+
+    @property
+    def n_bucket(self) -> int:
+        return self.offsets[-1]
+
+    def reduce_bytes(self) -> int:
+        """Algorithmic bytes of the fused reduce + SGD: W replicas read, parameters and
+        momentum read and written, valid elements only."""
+        w = self.workload
+        return (w.W * w.grad_bytes + 16) * w.n_elems
+
+    def pack_bytes(self) -> int:
+        return 2 * self.workload.grad_bytes * self.workload.n_elems
+
+    def unpack_bytes(self) -> int:
+        return 2 * 4 * self.workload.n_elems
+
+    def make_app(self, compute: Optional[Callable[[int], None]] = None,
+                 use_found_inf: bool = False) -> xs.App:
+        w = self.workload
+        return xs.App(self.gplan, self.pplan, self.grad_tables, self.buckets, self.params,
+                      self.momentum, self.param_table, w.lr, w.momentum, w.weight_decay,
+                      1.0 / w.loss_scale, self.found_inf if use_found_inf else None, compute)
+
+
+def make_task(w: wl.Workload, device="cuda", align: int = DEFAULT_ALIGN,
+              shared_grads: bool = False) -> TaskState:
+    """Allocate and fill everything one task's synchronisation touches.
+
+    shared_grads=True makes all W workers' tensor lists point at worker 0's tensors
+    (saves memory in timing runs of the largest workload; the buckets stay distinct).
+    """
+    dev = torch.device(device)
+    offsets = xs.bucket_layout(w.numel, align)
+    gplan = xs.Plan(w.numel, offsets, w.torch_grad_dtype)
+    pplan = xs.Plan(w.numel, offsets, torch.float32)
+    grads = []
+    for r in range(w.W):
+        if shared_grads and r > 0:
+            grads.append(grads[0])
+        else:
+            grads.append(wl.make_replica_grads(w, r, dev))
+    grad_tables = [xs.pointer_table(g, dev) for g in grads]
+    n_bucket = offsets[-1]
+    buckets = [torch.empty(n_bucket, dtype=w.torch_grad_dtype, device=dev) for _ in range(w.W)]
+    param_tensors = wl.make_params(w, dev)
+    param_table = xs.pointer_table(param_tensors, dev)
+    params = torch.zeros(n_bucket, dtype=torch.float32, device=dev)
+    xs.fuse_pack(pplan, param_table, params)            # parameters enter the bucket layout
+    momentum = torch.zeros(n_bucket, dtype=torch.float32, device=dev)
+    found_inf = torch.zeros(1, dtype=torch.int32, device=dev)
+    torch.cuda.synchronize(dev)
+    return TaskState(w, align, offsets, gplan, pplan, grads, grad_tables, buckets, param_tensors,
+                     param_table, params, momentum, found_inf)

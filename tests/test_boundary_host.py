@@ -1,0 +1,126 @@
+"""Host-side checks of the C-ABI library that need no GPU: the library loads, exports
+every function the header declares, and rejects bad arguments before launching."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2103_07974_amd import xs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "xs.h")
+
+FAKE = 0x7f0000001000          # never dereferenced: validation fails first
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(xs_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    L = xs.lib()
+    names = _declared_functions()
+    assert {"xs_fuse_pack", "xs_fused_reduce_sgd", "xs_fuse_unpack", "xs_crossover_step"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(names) == set(xs.EXPORTS)
+
+
+def test_status_strings():
+    assert xs.status_string(0) == "XS_OK"
+    assert xs.status_string(-2) == "XS_ERR_ALIGNMENT"
+    assert xs.status_string(-99) == "XS_ERR_UNKNOWN"
+
+
+@pytest.mark.parametrize("align", [1, 2, 4, 64, 100])
+def test_layout_matches_oracle(align):
+    rng = np.random.default_rng(align)
+    numel = [int(v) for v in rng.integers(0, 5000, size=40)] + [0, 1, 64, 4096]
+    assert xs.bucket_layout(numel, align) == [int(v) for v in oracle.layout(numel, align)]
+
+
+def test_layout_errors():
+    with pytest.raises(xs.XsError) as e:
+        xs.bucket_layout([1, 2], 0)
+    assert e.value.status == xs.XS_ERR_INVALID_ARG
+    assert xs.bucket_layout([], 8) == [0]
+
+
+def _reduce(W=2, dtype=xs.XS_F32, n=16, params=FAKE, mom=FAKE + 0x1000, pout=None, mout=None,
+            reps=None, hp=True, flag=None):
+    L = xs.lib()
+    reps = [FAKE + 0x10000 * (i + 2) for i in range(W)] if reps is None else reps
+    arr = (ctypes.c_void_p * max(len(reps), 1))(*reps)
+    h = xs.SgdHparams(0.1, 0.9, 0.0, 1.0)
+    return L.xs_fused_reduce_sgd(arr, W, dtype, n, params, mom, pout, mout,
+                                 ctypes.byref(h) if hp else None, flag, None)
+
+
+def test_reduce_argument_validation():
+    assert _reduce(W=0) == xs.XS_ERR_INVALID_ARG
+    assert _reduce(W=xs.XS_MAX_REPLICAS + 1) == xs.XS_ERR_INVALID_ARG
+    assert "W = 33" in xs.last_error()
+    assert _reduce(dtype=7) == xs.XS_ERR_UNSUPPORTED
+    assert _reduce(hp=False) == xs.XS_ERR_INVALID_ARG
+    assert _reduce(params=None) == xs.XS_ERR_INVALID_ARG
+    assert _reduce(params=FAKE + 4) == xs.XS_ERR_ALIGNMENT
+    assert _reduce(mom=FAKE + 0x1008) == xs.XS_ERR_ALIGNMENT
+    assert _reduce(reps=[FAKE + 0x20000, FAKE + 0x30002]) == xs.XS_ERR_ALIGNMENT
+    assert _reduce(reps=[FAKE + 0x20000, None]) == xs.XS_ERR_INVALID_ARG
+    assert _reduce(pout=FAKE + 0x4000, mout=None) == xs.XS_ERR_INVALID_ARG
+    assert _reduce(flag=FAKE + 0x9002) == xs.XS_ERR_ALIGNMENT
+    # aliasing: momentum inside params, a replica on top of params
+    assert _reduce(mom=FAKE + 16, n=16) == xs.XS_ERR_INVALID_ARG
+    assert _reduce(reps=[FAKE, FAKE + 0x20000]) == xs.XS_ERR_INVALID_ARG
+    assert _reduce(pout=FAKE + 0x1000, mout=FAKE + 0x5000) == xs.XS_ERR_INVALID_ARG
+    # n_elems == 0 is a valid no-op even with no buffers
+    assert _reduce(n=0, params=None, mom=None) == xs.XS_OK
+
+
+def test_pack_unpack_reject_bad_handles():
+    L = xs.lib()
+    assert L.xs_fuse_pack(None, FAKE, FAKE, None, None) == xs.XS_ERR_INVALID_ARG
+    assert L.xs_fuse_unpack(None, FAKE, FAKE, None) == xs.XS_ERR_INVALID_ARG
+    junk = ctypes.create_string_buffer(256)
+    assert L.xs_fuse_pack(ctypes.addressof(junk), FAKE, FAKE, None, None) == xs.XS_ERR_INVALID_ARG
+    assert L.xs_plan_destroy(None) == xs.XS_OK
+    assert L.xs_app_destroy(None) == xs.XS_OK
+    assert L.xs_plan_bucket_elems(None) == 0
+    assert L.xs_crossover_step(None, None, None, None) == xs.XS_ERR_INVALID_ARG
+    assert L.xs_crossover_drain(None, None) == xs.XS_ERR_INVALID_ARG
+    assert L.xs_app_sync(None, None) == xs.XS_ERR_INVALID_ARG
+
+
+def test_plan_create_validates_before_touching_the_device():
+    L = xs.lib()
+    h = ctypes.c_void_p()
+    u64 = ctypes.c_uint64
+
+    def create(numel, offsets, dtype=xs.XS_F32):
+        a = (u64 * max(len(numel), 1))(*numel)
+        o = (u64 * len(offsets))(*offsets)
+        return L.xs_plan_create(a, o, len(numel), dtype, ctypes.byref(h))
+
+    assert create([4, 4], [0, 4, 6]) == xs.XS_ERR_SIZE          # second tensor overruns
+    assert "overruns" in xs.last_error()
+    assert create([4, 4], [0, 8, 4]) == xs.XS_ERR_SIZE          # not monotone
+    assert create([4], [1, 5]) == xs.XS_ERR_SIZE                # must start at 0
+    assert create([4], [0, 4], dtype=9) == xs.XS_ERR_UNSUPPORTED
+    assert L.xs_plan_create(None, None, 0, 0, ctypes.byref(h)) == xs.XS_ERR_INVALID_ARG
+    assert L.xs_plan_create(None, None, 0, 0, None) == xs.XS_ERR_INVALID_ARG
+
+
+def test_tuning_roundtrip_and_range():
+    old = xs.tuning_get(xs.TUNE_REDUCE_WG_PER_CU)
+    xs.tuning_set(xs.TUNE_REDUCE_WG_PER_CU, 4)
+    assert xs.tuning_get(xs.TUNE_REDUCE_WG_PER_CU) == 4
+    xs.tuning_set(xs.TUNE_REDUCE_WG_PER_CU, old)
+    with pytest.raises(xs.XsError):
+        xs.tuning_set(xs.TUNE_REDUCE_WG_PER_CU, 1000)
+    with pytest.raises(xs.XsError):
+        xs.tuning_set(99, 1)

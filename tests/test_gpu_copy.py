@@ -1,0 +1,159 @@
+"""Parity of xs_fuse_pack / xs_fuse_unpack with the oracle: bit-exact, through the C-ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2103_07974_amd import xs
+
+pytestmark = pytest.mark.gpu
+
+# sizes in elements: empty, tiny, one-vector edges, around one 16 KiB chunk (4096 fp32 /
+# 8192 fp16 elements), several chunks with a ragged tail
+SIZES = [0, 1, 3, 5, 17, 63, 64, 65, 4095, 4096, 4097, 8191, 8192, 8193, 12289, 50001, 3, 0, 70000]
+GUARD = 8
+
+
+def _bits(a: np.ndarray) -> np.ndarray:
+    return a.view(np.uint32 if a.dtype.itemsize == 4 else np.uint16)
+
+
+def _random_bits(rng, n, np_dtype):
+    """Arbitrary finite-or-not bit patterns (NaN payloads, -0.0, subnormals)."""
+    it = np.dtype(np_dtype).itemsize
+    raw = rng.integers(0, 2 ** (8 * it), size=n, dtype=np.uint64)
+    return raw.astype(np.uint32 if it == 4 else np.uint16).view(np_dtype)
+
+
+def _device_tensors(host_list, torch_dtype, skew_elems):
+    """Each tensor lives inside its own allocation at an element offset (unaligned base),
+    with guard elements on both sides holding a canary."""
+    holders, views = [], []
+    for i, h in enumerate(host_list):
+        sk = (skew_elems * (i + 1)) % 7 if skew_elems else 0
+        buf = torch.full((h.size + 2 * GUARD + sk,), 7.0, dtype=torch_dtype, device="cuda")
+        v = buf[GUARD + sk: GUARD + sk + h.size]
+        v.copy_(torch.from_numpy(h.copy()).view(torch_dtype))
+        holders.append(buf)
+        views.append(v)
+    return holders, views
+
+
+@pytest.mark.parametrize("torch_dtype,np_dtype", [(torch.float32, np.float32), (torch.float16, np.float16)])
+@pytest.mark.parametrize("align", [1, 4, 64])
+@pytest.mark.parametrize("skew", [0, 1])
+def test_pack_and_unpack_bit_exact(torch_dtype, np_dtype, align, skew):
+    print(f"case dtype={torch_dtype} align={align} skew={skew}", flush=True)
+    rng = np.random.default_rng(100 + align + skew)
+    host = [_random_bits(rng, n, np_dtype) for n in SIZES]
+    numel = [h.size for h in host]
+    offs = xs.bucket_layout(numel, align)
+    assert offs == [int(v) for v in oracle.layout(numel, align)]
+    want_bucket = oracle.pack(host, np.asarray(offs, dtype=np.uint64))
+
+    holders, views = _device_tensors(host, torch_dtype, skew)
+    table = xs.pointer_table(views)
+    plan = xs.Plan(numel, offs, torch_dtype)
+    assert plan.bucket_elems == offs[-1] and plan.n_tensors == len(numel)
+    # bucket with guard zones and garbage inside
+    raw = torch.full((offs[-1] + 2 * GUARD,), 3.0, dtype=torch_dtype, device="cuda")
+    assert raw.data_ptr() % 16 == 0
+    bucket = raw[GUARD:GUARD + offs[-1]] if (GUARD * raw.element_size()) % 16 == 0 else None
+    assert bucket is not None
+    xs.fuse_pack(plan, table, bucket)
+    torch.cuda.synchronize()
+    got = bucket.cpu().numpy()
+    assert np.array_equal(_bits(got), _bits(want_bucket))
+    edge = raw.cpu().numpy()
+    assert np.all(edge[:GUARD] == 3.0) and np.all(edge[GUARD + offs[-1]:] == 3.0)
+
+    # unpack into fresh garbage-filled tensors; guards must survive
+    out_holders, out_views = _device_tensors([np.zeros(n, np_dtype) for n in numel], torch_dtype, skew)
+    for v in out_views:
+        v.fill_(5.0)
+    out_table = xs.pointer_table(out_views)
+    xs.fuse_unpack(plan, bucket, out_table)
+    torch.cuda.synchronize()
+    want_tensors = oracle.unpack(want_bucket, numel, np.asarray(offs, dtype=np.uint64))
+    for h, v, hold, wt in zip(host, out_views, out_holders, want_tensors):
+        g = v.cpu().numpy()
+        assert np.array_equal(_bits(g), _bits(h))
+        assert np.array_equal(_bits(g), _bits(wt))
+        whole = hold.cpu().numpy()
+        start = (v.data_ptr() - hold.data_ptr()) // hold.element_size()
+        assert np.all(whole[:start] == 7.0) and np.all(whole[start + h.size:] == 7.0)
+    plan.destroy()
+
+
+def test_empty_list_and_all_empty_tensors_are_noops():
+    for numel in ([], [0, 0, 0]):
+        offs = xs.bucket_layout(numel, 64)
+        plan = xs.Plan(numel, offs, torch.float32)
+        assert plan.bucket_elems == 0
+        dummy = torch.zeros(4, device="cuda")
+        table = xs.pointer_table([dummy] * max(len(numel), 1))
+        xs.fuse_pack(plan, table, dummy)
+        xs.fuse_unpack(plan, dummy, table)
+        torch.cuda.synchronize()
+        plan.destroy()
+
+
+def test_many_tensors_use_the_global_table_path():
+    # more tensors than the LDS copy of the table holds
+    rng = np.random.default_rng(5)
+    numel = [int(v) for v in rng.integers(0, 9, size=9000)]
+    host = [rng.standard_normal(n).astype(np.float32) for n in numel]
+    offs = xs.bucket_layout(numel, 1)
+    flat = torch.from_numpy(np.concatenate(host)).cuda()
+    views, pos = [], 0
+    for n in numel:
+        views.append(flat[pos:pos + n]); pos += n
+    table = xs.pointer_table(views)
+    plan = xs.Plan(numel, offs, torch.float32)
+    bucket = torch.empty(offs[-1], dtype=torch.float32, device="cuda")
+    xs.fuse_pack(plan, table, bucket)
+    torch.cuda.synchronize()
+    want = oracle.pack(host, np.asarray(offs, dtype=np.uint64))
+    assert np.array_equal(_bits(bucket.cpu().numpy()), _bits(want))
+    plan.destroy()
+
+
+@pytest.mark.parametrize("torch_dtype,np_dtype", [(torch.float16, np.float16), (torch.float32, np.float32)])
+def test_pack_raises_the_overflow_flag(torch_dtype, np_dtype):
+    numel = [5, 9000, 33, 20000]
+    align = 8
+    offs = xs.bucket_layout(numel, align)
+    plan = xs.Plan(numel, offs, torch_dtype)
+    rng = np.random.default_rng(17)
+    base = [rng.standard_normal(n).astype(np_dtype) for n in numel]
+    bucket = torch.empty(offs[-1], dtype=torch_dtype, device="cuda")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+
+    def run(host):
+        views = [torch.from_numpy(h).cuda() for h in host]
+        flag.zero_()
+        xs.fuse_pack(plan, xs.pointer_table(views), bucket, flag)
+        torch.cuda.synchronize()
+        want = oracle.any_nonfinite([oracle.pack(host, np.asarray(offs, dtype=np.uint64))], numel,
+                                    np.asarray(offs, dtype=np.uint64))
+        return int(flag.item()), int(want)
+
+    assert run(base) == (0, 0)
+    # head element, vector body, chunk edge, last element; inf, -inf, NaN
+    for t, k, bad in [(0, 0, np.inf), (0, 4, -np.inf), (1, 4500, np.nan), (1, 8191, np.inf),
+                      (1, 8999, np.nan), (2, 32, -np.inf), (3, 19999, np.inf), (3, 16384, np.nan)]:
+        host = [b.copy() for b in base]
+        host[t][k] = bad
+        assert run(host) == (1, 1), (t, k, bad)
+    # the largest finite values do not raise it
+    host = [b.copy() for b in base]
+    host[1][:4] = np.array([np.finfo(np_dtype).max, -np.finfo(np_dtype).max,
+                            np.finfo(np_dtype).tiny, -0.0], np_dtype)
+    assert run(host) == (0, 0)
+    # the flag is sticky: a clean pack does not clear it
+    flag.fill_(1)
+    views = [torch.from_numpy(h).cuda() for h in base]
+    xs.fuse_pack(plan, xs.pointer_table(views), bucket, flag)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 1
+    plan.destroy()

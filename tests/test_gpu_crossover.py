@@ -1,0 +1,167 @@
+"""The two-stream crossover driver against Algorithm 1 executed by the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import schedule
+from paper_2103_07974_amd import harness, workloads as wl, xs
+
+pytestmark = pytest.mark.gpu
+
+
+def _mini(name, shapes, W):
+    return wl.scaled(wl.RESNET50, name, shapes, W=W)
+
+
+def _coef(w):
+    return np.float32(0.5 ** (w + 1))
+
+
+def _device_compute(task, counter):
+    """Gradients that depend on the current parameters, so a computation that ran before
+    its task's previous update had landed would change the result.  Only exactly rounded
+    fp32 multiply and add are used, which numpy reproduces bit for bit."""
+    def fn(stream_ptr):
+        counter[0] += 1
+        t = np.float32(counter[0])
+        s = torch.cuda.ExternalStream(stream_ptr) if stream_ptr else torch.cuda.default_stream()
+        with torch.cuda.stream(s):
+            for w, glist in enumerate(task.grads):
+                for g, p in zip(glist, task.param_tensors):
+                    torch.mul(p, float(_coef(w)), out=g)
+                    g.add_(float(t) * 1e-3)
+    return fn
+
+
+def _host_compute(params, W, t):
+    k = np.float32(float(np.float32(t)) * 1e-3)     # the scalar the device adds, rounded once to fp32
+    return [[(p * _coef(w) + k).astype(np.float32) for p in params] for w in range(W)]
+
+
+def _run_gpu(workloads, T, align):
+    tasks = [harness.make_task(w, "cuda", align) for w in workloads]
+    counters = [[0] for _ in tasks]
+    apps = [t.make_app(_device_compute(t, c)) for t, c in zip(tasks, counters)]
+    cs, ss = torch.cuda.Stream(), torch.cuda.Stream()
+    N = len(apps)
+    outstanding = set()
+    log = []
+    for t in range(1, T + 1):
+        for i in range(N):
+            n = (i + 1) % N
+            if N == 1:
+                xs.crossover_step(apps[0], apps[0], cs, ss)
+                log.append(("update", 0, t))
+                continue
+            # Algorithm 1 for two tasks: task i computes while task n's previous gradients
+            # are synchronised; n has nothing outstanding only in the first iteration
+            sync = apps[n] if n in outstanding else None
+            xs.crossover_step(apps[i], sync, cs, ss)
+            outstanding.add(i)
+            if sync is not None:
+                outstanding.discard(n)
+    for n in sorted(outstanding):
+        xs.crossover_drain(apps[n], ss)
+    torch.cuda.synchronize()
+    return tasks, apps, counters
+
+
+def _run_oracle(workloads, T, align, tasks):
+    state = {"p": [[p.cpu().numpy().copy() for p in wl.make_params(w, "cuda")] for w in workloads],
+             "v": [np.zeros(t.n_bucket, np.float32) for t in tasks],
+             "count": [0] * len(workloads)}
+
+    def compute(i, t):
+        state["count"][i] += 1
+        return _host_compute(state["p"][i], workloads[i].W, state["count"][i])
+
+    def sync_update(i, g):
+        w = workloads[i]
+        newp, _ = oracle.sync_step(g, state["p"][i], state["v"][i], np.float32(w.lr).item(),
+                                   np.float32(w.momentum).item(),
+                                   np.float32(w.weight_decay).item(), 1.0, align=align,
+                                   precision="f32")
+        state["p"][i] = newp
+    log = schedule.run_crossover(len(workloads), T, compute, sync_update)
+    return state, log
+
+
+@pytest.mark.parametrize("T", [1, 4])
+def test_two_tasks_match_algorithm_1(T):
+    wls = [_mini("a", [(300, 7), (64,), (5000,)], W=2), _mini("b", [(17,), (9000, 3)], W=4)]
+    tasks, apps, counters = _run_gpu(wls, T, align=8)
+    state, log = _run_oracle(wls, T, 8, tasks)
+    assert [c[0] for c in counters] == [T, T]
+    assert sum(1 for e in log if e[0] in ("update", "drain")) == 2 * T
+    for i, task in enumerate(tasks):
+        for got, want in zip(task.param_tensors, state["p"][i]):
+            assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
+        assert np.array_equal(task.momentum.cpu().numpy().view(np.uint32),
+                              state["v"][i].view(np.uint32))
+    for a in apps:
+        a.destroy()
+
+
+def test_single_task_degenerates_to_compute_then_sync():
+    wls = [_mini("solo", [(1000,), (33,)], W=2)]
+    tasks, apps, counters = _run_gpu(wls, 3, align=4)
+    state, _ = _run_oracle(wls, 3, 4, tasks)
+    for got, want in zip(tasks[0].param_tensors, state["p"][0]):
+        assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    apps[0].destroy()
+
+
+def test_out_of_order_calls_are_refused():
+    wls = [_mini("a", [(100,)], W=2), _mini("b", [(50,)], W=2)]
+    tasks = [harness.make_task(w, "cuda") for w in wls]
+    apps = [t.make_app() for t in tasks]
+    cs, ss = torch.cuda.Stream(), torch.cuda.Stream()
+    with pytest.raises(xs.XsError) as e:
+        xs.crossover_step(apps[0], apps[1], cs, ss)           # b never computed
+    assert e.value.status == xs.XS_ERR_STATE
+    with pytest.raises(xs.XsError) as e:
+        xs.crossover_drain(apps[0], ss)
+    assert e.value.status == xs.XS_ERR_STATE
+    xs.crossover_step(apps[0], None, cs, ss)                  # first-iteration bypass
+    xs.crossover_step(apps[1], apps[0], cs, ss)
+    with pytest.raises(xs.XsError):
+        xs.crossover_drain(apps[0], ss)                       # already synchronised
+    xs.crossover_drain(apps[1], ss)
+    apps[0].wait_sync(None); apps[1].wait_sync(None)
+    torch.cuda.synchronize()
+    for a in apps:
+        a.destroy()
+
+
+def test_sync_overlaps_the_other_tasks_compute():
+    """With a long computation on the compute stream, the other task's synchronisation
+    finishes while that computation is still running."""
+    wa = _mini("a", [(1 << 20,)], W=2)
+    wb = _mini("b", [(1 << 20,)], W=2)
+    ta, tb = harness.make_task(wa, "cuda"), harness.make_task(wb, "cuda")
+    m = torch.randn(4096, 4096, device="cuda", dtype=torch.bfloat16)
+    out = torch.empty_like(m)
+    done = {}
+
+    def long_compute(stream_ptr):
+        s = torch.cuda.ExternalStream(stream_ptr)
+        with torch.cuda.stream(s):
+            for _ in range(60):
+                torch.matmul(m, m, out=out)
+
+    a = ta.make_app(long_compute)
+    b = tb.make_app(None)
+    cs, ss = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    xs.crossover_step(b, None, cs, ss)            # b "computes" (nothing) -> gradients outstanding
+    xs.crossover_step(a, b, cs, ss)               # a computes for a while; b synchronises beside it
+    e_sync = torch.cuda.Event(); e_comp = torch.cuda.Event()
+    b.wait_sync(ss); e_sync.record(ss)
+    e_comp.record(cs)
+    while not e_sync.query():
+        pass
+    done["compute_finished_when_sync_done"] = e_comp.query()
+    torch.cuda.synchronize()
+    assert done["compute_finished_when_sync_done"] is False
+    a.destroy(); b.destroy()
