@@ -179,20 +179,35 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_anyw_kernel(
         const int cnt = (n - base) < (uint64_t)VEC ? (int)(n - base) : VEC;
         float s[VEC];
         if (cnt == VEC) {
-#pragma unroll 4
-            for (uint32_t w = 0; w < W; ++w) {
-                const u32x4 g = *(const u32x4 *)((const char *)reps.p[w] + base * (F16 ? 2 : 4));
+            const uint64_t byte_off = base * (F16 ? 2 : 4);
+            {
+                const u32x4 g = *(const u32x4 *)((const char *)reps.p[0] + byte_off);
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
+                    const uint32_t bits = g[q];   // a scalar copy: bit_cast of a vector element misreads
                     if constexpr (F16) {
-                        if constexpr (DETECT) bad |= nonfinite_f16x2(g[q]);
-                        const float lo = half_lo(g[q]), hi = half_hi(g[q]);
-                        s[2 * q] = (w == 0) ? lo : s[2 * q] + lo;
-                        s[2 * q + 1] = (w == 0) ? hi : s[2 * q + 1] + hi;
+                        if constexpr (DETECT) bad |= nonfinite_f16x2(bits);
+                        s[2 * q] = half_lo(bits);
+                        s[2 * q + 1] = half_hi(bits);
                     } else {
-                        if constexpr (DETECT) bad |= nonfinite_f32(g[q]);
-                        const float f = __builtin_bit_cast(float, g[q]);
-                        s[q] = (w == 0) ? f : s[q] + f;
+                        if constexpr (DETECT) bad |= nonfinite_f32(bits);
+                        s[q] = __builtin_bit_cast(float, bits);
+                    }
+                }
+            }
+#pragma unroll 4
+            for (uint32_t w = 1; w < W; ++w) {
+                const u32x4 g = *(const u32x4 *)((const char *)reps.p[w] + byte_off);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t bits = g[q];
+                    if constexpr (F16) {
+                        if constexpr (DETECT) bad |= nonfinite_f16x2(bits);
+                        s[2 * q] = s[2 * q] + half_lo(bits);
+                        s[2 * q + 1] = s[2 * q + 1] + half_hi(bits);
+                    } else {
+                        if constexpr (DETECT) bad |= nonfinite_f32(bits);
+                        s[q] = s[q] + __builtin_bit_cast(float, bits);
                     }
                 }
             }

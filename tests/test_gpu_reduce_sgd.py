@@ -38,13 +38,15 @@ def _oracle(reps_np, x_np, v_np, inv=1.0, lr=LR, mu=MU, wd=WD):
 
 
 def _assert_close(got, want64, f16):
+    # half-precision gradients are widened exactly and everything after that is fp32, so
+    # the fp32 bar holds for them too; the 2e-3 relative bar is checked where a relative
+    # error is meaningful (away from results that happen to land next to zero)
     err = np.abs(got.astype(np.float64) - want64)
-    if f16:
-        tol = RTOL16 * np.abs(want64) + 1e-12
-    else:
-        tol = ATOL32 + RTOL32 * np.abs(want64)
-    bad = err > tol
+    bad = err > ATOL32 + RTOL32 * np.abs(want64)
     assert not bad.any(), f"{bad.sum()} elements out of tolerance, worst {err.max():.3e}"
+    if f16:
+        big = np.abs(want64) > 1e-4
+        assert np.all(err[big] <= RTOL16 * np.abs(want64[big]))
 
 
 def _ulp_distance(a, b):
