@@ -1,0 +1,319 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused gradient-synchronisation path on one MI355X.
+
+A step is one whole synchronisation of the ResNet-50-shaped gradient set: W = 8 packs,
+the fused reduce + SGD, and the unpack of the parameters, on one stream, inputs resident
+in HBM.  `value` is (W*s + 16) * N bytes (W replica buckets, parameters and momentum read,
+parameters and momentum written) divided by the time of the whole step.  `roofline`
+covers the fused reduce + SGD kernel alone, timed with events inside the timed region.
+The VGG-16- and BERT-large-shaped sets, the tiny set's latency and the two-stream
+crossover pair are measured after the timed region and reported under `extra`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def _median(xs_):
+    s = sorted(xs_)
+    return s[len(s) // 2] if len(s) % 2 else 0.5 * (s[len(s) // 2 - 1] + s[len(s) // 2])
+
+
+def time_steps(tasks, steps, warmup, stream):
+    """K whole steps, rotating over independent buffer sets so that no step finds its
+    state in the 256 MB last-level cache; events around the reduce kernel of each step."""
+    import torch
+    from paper_2103_07974_amd import xs
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(steps)]
+
+    def one(task, pair=None):
+        w = task.workload
+        for r in range(w.W):
+            xs.fuse_pack(task.gplan, task.grad_tables[r], task.buckets[r], None, stream)
+        if pair:
+            pair[0].record(stream)
+        xs.fused_reduce_sgd(task.buckets, task.n_bucket, task.params, task.momentum,
+                            w.lr, w.momentum, w.weight_decay, 1.0 / w.loss_scale, stream=stream)
+        if pair:
+            pair[1].record(stream)
+        xs.fuse_unpack(task.pplan, task.params, task.param_table, stream)
+
+    with torch.cuda.stream(stream):
+        for i in range(warmup):
+            one(tasks[i % len(tasks)])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            one(tasks[i % len(tasks)], ev[i])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    kernel_ms = [a.elapsed_time(b) for a, b in ev]
+    return (t1 - t0) * 1e3 / steps, kernel_ms
+
+
+def time_kernels(task, stream, reps=30, warm=5):
+    """Per-kernel medians (ms) for pack (one replica), reduce + SGD, unpack."""
+    import torch
+    from paper_2103_07974_amd import xs
+    w = task.workload
+    out = {}
+
+    def run(fn):
+        ts = []
+        with torch.cuda.stream(stream):
+            for i in range(warm + reps):
+                a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+                a.record(stream); fn(i); b.record(stream)
+                b.synchronize()
+                if i >= warm:
+                    ts.append(a.elapsed_time(b))
+        return ts
+
+    out["pack_ms"] = _median(run(lambda i: xs.fuse_pack(
+        task.gplan, task.grad_tables[i % w.W], task.buckets[i % w.W], None, stream)))
+    red = run(lambda i: xs.fused_reduce_sgd(
+        task.buckets, task.n_bucket, task.params, task.momentum, w.lr, w.momentum,
+        w.weight_decay, 1.0 / w.loss_scale, stream=stream))
+    out["reduce_sgd_ms"] = _median(red)
+    out["reduce_sgd_min_ms"] = min(red)
+    out["unpack_ms"] = _median(run(lambda i: xs.fuse_unpack(
+        task.pplan, task.params, task.param_table, stream)))
+    out["reduce_sgd_GBs"] = task.reduce_bytes() / out["reduce_sgd_ms"] / 1e6
+    out["reduce_sgd_frac_of_hbm_peak"] = out["reduce_sgd_GBs"] / HBM_PEAK_GBS
+    out["pack_GBs"] = task.pack_bytes() / out["pack_ms"] / 1e6
+    out["unpack_GBs"] = task.unpack_bytes() / out["unpack_ms"] / 1e6
+    return out
+
+
+def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192):
+    """Two tasks alternate as in Algorithm 1: one computes (a chain of bf16 GEMMs standing in
+    for forward + backward) while the other synchronises on the second stream."""
+    import torch
+    from paper_2103_07974_amd import xs
+    g = torch.Generator(device="cuda"); g.manual_seed(task_a.workload.seed + 100)
+    B = (torch.randn(dim, dim, generator=g, device="cuda") / dim ** 0.5).to(torch.bfloat16)
+    Y = [torch.randn(dim, dim, generator=g, device="cuda").to(torch.bfloat16) for _ in range(2)]
+
+    def compute(stream_ptr):
+        s = torch.cuda.ExternalStream(stream_ptr)
+        with torch.cuda.stream(s):
+            for k in range(chain):
+                torch.matmul(Y[k & 1], B, out=Y[1 - (k & 1)])
+
+    apps = [task_a.make_app(compute), task_b.make_app(compute)]
+    cs, ss = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def run_cross(record=None):
+        # Algorithm 1, N = 2, T outer iterations: the first inner step has nothing to
+        # receive, every later one synchronises the task that computed before it, and the
+        # last task's gradients are drained at the end: 2T computations, 2T synchronisations
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        xs.crossover_step(apps[0], None, cs, ss)
+        for k in range(1, 2 * T):
+            i = k % 2
+            xs.crossover_step(apps[i], apps[1 - i], cs, ss)
+            if record is not None:
+                es = torch.cuda.Event(enable_timing=True); ec = torch.cuda.Event(enable_timing=True)
+                es.record(ss); ec.record(cs)
+                record.append((1 - i, es, ec))
+        xs.crossover_drain(apps[1], ss)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3
+
+    def run_serial():
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(T):
+            for i in (0, 1):
+                compute(cs.cuda_stream)
+                apps[i].sync(cs)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3
+
+    def run_comp():
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(2 * T):
+            compute(cs.cuda_stream)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3
+
+    def run_sync(app, n=10):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            app.sync(ss)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    run_comp(); run_serial(); run_cross()                    # warm-up of every mode
+    t_comp = _median([run_comp() for _ in range(3)])
+    t_serial = _median([run_serial() for _ in range(3)])
+    rec = []
+    t_cross = _median([run_cross(), run_cross(), run_cross(rec)])
+    sync_a, sync_b = run_sync(apps[0]), run_sync(apps[1])
+    sum_sync = t_serial - t_comp
+    # event view: how long each synchronisation ran past the end of the computation beside it
+    exposed = {0: 0.0, 1: 0.0}; count = {0: 0, 1: 0}; late = {0: 0, 1: 0}
+    for who, es, ec in rec:
+        d = ec.elapsed_time(es)            # > 0: the sync finished after the compute beside it
+        count[who] += 1
+        if d > 0:
+            exposed[who] += d; late[who] += 1
+    res = {
+        "T": T, "gemm_chain": f"{chain}x[{dim}x{dim}]@[{dim}x{dim}] bf16",
+        "t_comp_ms": t_comp, "t_serial_ms": t_serial, "t_cross_ms": t_cross,
+        "sum_sync_ms": sum_sync, "sync_a_alone_ms": sync_a, "sync_b_alone_ms": sync_b,
+        "compute_chain_ms": t_comp / (2 * T),
+        "comm_comp_ratio_a": sync_a / (t_comp / (2 * T)), "comm_comp_ratio_b": sync_b / (t_comp / (2 * T)),
+        "hidden_fraction": 1.0 - (t_cross - t_comp) / sum_sync if sum_sync > 0 else None,
+        "speedup_vs_serial": t_serial / t_cross,
+        "syncs_finished_before_compute_end": {"a": count[0] - late[0], "b": count[1] - late[1],
+                                              "of_a": count[0], "of_b": count[1]},
+        "hidden_b_by_events": 1.0 - exposed[1] / (count[1] * sync_b) if count[1] else None,
+        "hidden_a_by_events": 1.0 - exposed[0] / (count[0] * sync_a) if count[0] else None,
+    }
+    for a in apps:
+        a.destroy()
+    return res
+
+
+def cpu_baseline(w, align, budget_s=20.0):
+    """The oracle as it stands, one thread, on the same workload (bounded sample)."""
+    import numpy as np
+    import oracle
+    from paper_2103_07974_amd import workloads as wl
+    grads = [[t.numpy() for t in wl.make_replica_grads(w, r)] for r in range(w.W)]
+    params = [t.numpy() for t in wl.make_params(w)]
+    offs = oracle.layout(w.numel, align)
+    v = np.zeros(int(offs[-1]))
+    lr, mu, wd = (np.float32(w.lr).item(), np.float32(w.momentum).item(),
+                  np.float32(w.weight_decay).item())
+    steps, t_total = 0, 0.0
+    while steps < 2 or (t_total < budget_s and steps < 50):
+        t0 = time.perf_counter()
+        params, _ = oracle.sync_step(grads, params, v, lr, mu, wd, 1.0 / w.loss_scale, align=align)
+        params = [p.astype(np.float32) for p in params]
+        t_total += time.perf_counter() - t0
+        steps += 1
+    ms = t_total * 1e3 / steps
+    bytes_ = (w.W * w.grad_bytes + 16) * w.n_elems
+    return {"value": bytes_ / ms / 1e6, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "ms_per_step": ms,
+            "sample": f"{steps} whole {w.name} steps (W={w.W} packs, double-precision "
+                      f"reduce+SGD, unpack) of the C oracle, single thread, "
+                      f"{len(os.sched_getaffinity(0))} host cores available"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=6)
+    ap.add_argument("--quick", action="store_true", help="headline workload only")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the W workers' gradients are resident "
+              "on that GPU); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2103_07974_amd import harness, workloads as wl, xs
+    xs.lib()
+    torch.cuda.set_device(0)
+    stream = torch.cuda.Stream()
+
+    w = wl.RESNET50
+    tasks = [harness.make_task(w, "cuda") for _ in range(3)]
+    for t in tasks:   # steady state: momentum already non-zero
+        t.momentum.copy_(wl.make_flat(t.n_bucket, 0.01, w.seed + 77, device="cuda"))
+    ms_per_step, kernel_ms = time_steps(tasks, args.steps, args.warmup, stream)
+    k_avg = sum(kernel_ms) / len(kernel_ms)
+    reduce_bytes = tasks[0].reduce_bytes()
+    achieved = reduce_bytes / k_avg / 1e6
+    out = {
+        "metric": "fused grad-sync GB/s + % HBM roofline; crossover sync-hidden fraction (1 GPU)",
+        "value": reduce_bytes / ms_per_step / 1e6,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "resnet50-shaped gradient set, 161 tensors, 25,557,032 elements, "
+                               "W=8 fp32 replicas; step = 8 packs + fused reduce+SGD + unpack",
+                   "W": w.W, "n_elems": w.n_elems, "n_tensors": w.n_tensors,
+                   "bucket_align_elems": tasks[0].align,
+                   "bytes_per_step_counted": reduce_bytes},
+        "roofline": {"bound": "hbm", "kernel": "xs::reduce_sgd_kernel<8, false, false, true, true, true>",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": reduce_bytes, "avg_launch_ms": k_avg,
+                     "median_launch_ms": _median(kernel_ms), "min_launch_ms": min(kernel_ms)},
+    }
+    extra = {"resnet50": time_kernels(tasks[0], stream)}
+    del tasks
+    torch.cuda.empty_cache()
+
+    if not args.quick:
+        tiny = harness.make_task(wl.TINY_MLP, "cuda")
+        tk = time_kernels(tiny, stream)
+        app = tiny.make_app()
+        with torch.cuda.stream(stream):
+            for _ in range(20):
+                app.sync(stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(200):
+                app.sync(stream)
+            torch.cuda.synchronize()
+            tk["step_latency_us"] = (time.perf_counter() - t0) * 1e6 / 200
+        app.destroy()
+        extra["tiny_mlp"] = {k: tk[k] for k in ("pack_ms", "reduce_sgd_ms", "unpack_ms", "step_latency_us")}
+
+        ta = harness.make_task(wl.RESNET50, "cuda")
+        tb = harness.make_task(wl.VGG16, "cuda")
+        extra["vgg16"] = time_kernels(tb, stream)
+        with torch.cuda.stream(stream):
+            app = tb.make_app()
+            for _ in range(3):
+                app.sync(stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                app.sync(stream)
+            torch.cuda.synchronize()
+            extra["vgg16"]["step_ms"] = (time.perf_counter() - t0) * 1e3 / 10
+            app.destroy()
+        extra["crossover"] = crossover_pair(ta, tb)
+        del ta, tb
+        torch.cuda.empty_cache()
+
+        bert = harness.make_task(wl.BERT_LARGE_F16, "cuda", shared_grads=True)
+        extra["bert_large_f16"] = time_kernels(bert, stream, reps=15, warm=3)
+        del bert
+        torch.cuda.empty_cache()
+
+    out["extra"] = extra
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w, harness.DEFAULT_ALIGN)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -197,11 +197,15 @@ int xs_app_wait_sync(xs_app *app, void *hip_stream);
 
 /* ------------------------------------------------------------------------
  * Launch tuning (process-wide; defaults are the measured best for MI355X).
- * key: 0 = reduce kernel workgroups per compute unit (0 = one vector per thread,
- *          no grid-stride loop),
+ * key: 0 = reduce kernel workgroups per compute unit for a grid-stride launch
+ *          (0 = one 16-byte vector per lane, no loop),
  *      1 = pack/unpack workgroups per compute unit,
  *      2 = non-temporal loads of gradient replicas (0/1),
- *      3 = non-temporal stores of parameters and momentum (0/1).
+ *      3 = non-temporal stores of parameters and momentum (0/1),
+ *      4 = non-temporal loads of parameters and momentum (0/1),
+ *      5 = bytes of LDS reserved per reduce workgroup; the kernel does not use LDS,
+ *          the reservation only caps how many wavefronts share a compute unit.
+ *      Keys 2-5 also accept -1 (the default): chosen per gradient dtype.
  * Returns XS_ERR_INVALID_ARG for an unknown key or out-of-range value.
  */
 int xs_tuning_set(int key, int value);

@@ -42,7 +42,9 @@ int compute_units()
     return cus;
 }
 
-Tuning g_tuning = {/*reduce_wg_per_cu*/ 8, /*copy_wg_per_cu*/ 8, /*nt_loads*/ 1, /*nt_stores*/ 0};
+// -1 = chosen per gradient dtype at launch (see launch_reduce_sgd)
+Tuning g_tuning = {/*reduce_wg_per_cu*/ 0, /*copy_wg_per_cu*/ 8, /*nt_loads*/ -1, /*nt_stores*/ -1,
+                   /*nt_state_loads*/ -1, /*reduce_lds_reserve*/ -1};
 
 }  // namespace xs
 
@@ -70,8 +72,10 @@ extern "C" int xs_tuning_set(int key, int value)
     switch (key) {
     case 0: if (value < 0 || value > 64) break; g_tuning.reduce_wg_per_cu = value; return XS_OK;
     case 1: if (value < 1 || value > 64) break; g_tuning.copy_wg_per_cu = value; return XS_OK;
-    case 2: if (value < 0 || value > 1) break; g_tuning.nt_loads = value; return XS_OK;
-    case 3: if (value < 0 || value > 1) break; g_tuning.nt_stores = value; return XS_OK;
+    case 2: if (value < -1 || value > 1) break; g_tuning.nt_loads = value; return XS_OK;
+    case 3: if (value < -1 || value > 1) break; g_tuning.nt_stores = value; return XS_OK;
+    case 4: if (value < -1 || value > 1) break; g_tuning.nt_state_loads = value; return XS_OK;
+    case 5: if (value < -1 || value > 65536) break; g_tuning.reduce_lds_reserve = value; return XS_OK;
     default: return fail(XS_ERR_INVALID_ARG, "xs_tuning_set: unknown key %d", key);
     }
     return fail(XS_ERR_INVALID_ARG, "xs_tuning_set: value %d out of range for key %d", value, key);
@@ -85,6 +89,8 @@ extern "C" int xs_tuning_get(int key, int *value_out)
     case 1: *value_out = g_tuning.copy_wg_per_cu; return XS_OK;
     case 2: *value_out = g_tuning.nt_loads; return XS_OK;
     case 3: *value_out = g_tuning.nt_stores; return XS_OK;
+    case 4: *value_out = g_tuning.nt_state_loads; return XS_OK;
+    case 5: *value_out = g_tuning.reduce_lds_reserve; return XS_OK;
     default: return fail(XS_ERR_INVALID_ARG, "xs_tuning_get: unknown key %d", key);
     }
 }

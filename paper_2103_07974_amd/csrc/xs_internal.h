@@ -30,6 +30,8 @@ struct Tuning {
     int copy_wg_per_cu;
     int nt_loads;
     int nt_stores;
+    int nt_state_loads;
+    int reduce_lds_reserve;   // bytes of LDS reserved per reduce workgroup (occupancy throttle)
 };
 extern Tuning g_tuning;
 

@@ -19,7 +19,7 @@ namespace xs {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 64;   // one wavefront per workgroup: finest dispatch grain
 
 template <int N>
 struct ReplicaPtrs {
@@ -28,6 +28,13 @@ struct ReplicaPtrs {
 
 template <bool NT>
 __device__ __forceinline__ u32x4 load_g(const u32x4 *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+template <bool NT>
+__device__ __forceinline__ f32x4 load_s(const f32x4 *p)
 {
     if constexpr (NT) return __builtin_nontemporal_load(p);
     else return *p;
@@ -72,7 +79,7 @@ __device__ __forceinline__ void sgd(float g_sum, float c, float &x, float &v, fl
 
 // VEC elements per lane per trip: 4 (fp32 gradients) or 8 (fp16 gradients), so that
 // every gradient load is 16 bytes wide.
-template <int W, bool F16, bool DETECT, bool NTL, bool NTS>
+template <int W, bool F16, bool DETECT, bool NTL, bool NTS, bool NTX>
 __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(
     ReplicaPtrs<W> reps, uint64_t n, const float *x_in, const float *v_in,
     float *x_out, float *v_out, float lr, float mu, float wd, float c,
@@ -93,8 +100,8 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(
         f32x4 x[SV], v[SV];
 #pragma unroll
         for (int k = 0; k < SV; ++k) {
-            x[k] = ((const f32x4 *)x_in)[i * SV + k];
-            v[k] = ((const f32x4 *)v_in)[i * SV + k];
+            x[k] = load_s<NTX>((const f32x4 *)x_in + i * SV + k);
+            v[k] = load_s<NTX>((const f32x4 *)v_in + i * SV + k);
         }
         float s[VEC];
 #pragma unroll
@@ -252,31 +259,40 @@ struct LaunchArgs {
     float lr, mu, wd, c;
     int32_t *found_inf;
     dim3 grid;
+    unsigned lds_reserve;
     hipStream_t stream;
 };
 
-template <int W, bool F16, bool DETECT, bool NTL, bool NTS>
+template <int W, bool F16, bool DETECT, bool NTL, bool NTS, bool NTX>
 static void launch_one(const LaunchArgs &a)
 {
     ReplicaPtrs<W> r;
     for (int w = 0; w < W; ++w) r.p[w] = a.replicas[w];
-    hipLaunchKernelGGL((reduce_sgd_kernel<W, F16, DETECT, NTL, NTS>), a.grid, dim3(kThreads), 0,
-                       a.stream, r, a.n, a.x_in, a.v_in, a.x_out, a.v_out, a.lr, a.mu, a.wd, a.c,
-                       a.found_inf);
+    hipLaunchKernelGGL((reduce_sgd_kernel<W, F16, DETECT, NTL, NTS, NTX>), a.grid, dim3(kThreads),
+                       a.lds_reserve, a.stream, r, a.n, a.x_in, a.v_in, a.x_out, a.v_out, a.lr,
+                       a.mu, a.wd, a.c, a.found_inf);
 }
 
 template <int W, bool F16, bool DETECT>
-static void launch_nt(const LaunchArgs &a, bool ntl, bool nts)
+static void launch_nt(const LaunchArgs &a, int nt)
 {
-    if (ntl) { if (nts) launch_one<W, F16, DETECT, true, true>(a); else launch_one<W, F16, DETECT, true, false>(a); }
-    else     { if (nts) launch_one<W, F16, DETECT, false, true>(a); else launch_one<W, F16, DETECT, false, false>(a); }
+    switch (nt & 7) {
+    case 0: launch_one<W, F16, DETECT, false, false, false>(a); break;
+    case 1: launch_one<W, F16, DETECT, true, false, false>(a); break;
+    case 2: launch_one<W, F16, DETECT, false, true, false>(a); break;
+    case 3: launch_one<W, F16, DETECT, true, true, false>(a); break;
+    case 4: launch_one<W, F16, DETECT, false, false, true>(a); break;
+    case 5: launch_one<W, F16, DETECT, true, false, true>(a); break;
+    case 6: launch_one<W, F16, DETECT, false, true, true>(a); break;
+    default: launch_one<W, F16, DETECT, true, true, true>(a); break;
+    }
 }
 
 template <int W>
-static void launch_w(const LaunchArgs &a, bool f16, bool detect, bool ntl, bool nts)
+static void launch_w(const LaunchArgs &a, bool f16, bool detect, int nt)
 {
-    if (f16) { if (detect) launch_nt<W, true, true>(a, ntl, nts); else launch_nt<W, true, false>(a, ntl, nts); }
-    else     { if (detect) launch_nt<W, false, true>(a, ntl, nts); else launch_nt<W, false, false>(a, ntl, nts); }
+    if (f16) { if (detect) launch_nt<W, true, true>(a, nt); else launch_nt<W, true, false>(a, nt); }
+    else     { if (detect) launch_nt<W, false, true>(a, nt); else launch_nt<W, false, false>(a, nt); }
 }
 
 template <bool F16, bool DETECT>
@@ -284,7 +300,7 @@ static void launch_anyw(const LaunchArgs &a, uint32_t W)
 {
     ReplicaPtrs<XS_MAX_REPLICAS> r;
     for (uint32_t w = 0; w < XS_MAX_REPLICAS; ++w) r.p[w] = w < W ? a.replicas[w] : nullptr;
-    hipLaunchKernelGGL((reduce_sgd_anyw_kernel<F16, DETECT>), a.grid, dim3(kThreads), 0, a.stream,
+    hipLaunchKernelGGL((reduce_sgd_anyw_kernel<F16, DETECT>), a.grid, dim3(kThreads), a.lds_reserve, a.stream,
                        r, W, a.n, a.x_in, a.v_in, a.x_out, a.v_out, a.lr, a.mu, a.wd, a.c,
                        a.found_inf);
 }
@@ -317,14 +333,25 @@ int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64
     a.found_inf = found_inf;
     a.grid = dim3((unsigned)blocks);
     a.stream = stream;
-    const bool ntl = g_tuning.nt_loads != 0, nts = g_tuning.nt_stores != 0;
+    // Measured on MI355X: the pass is fastest with about 100-120 KB of loads in flight per
+    // compute unit; more wavefronts than that only disorder the DRAM access stream.  The
+    // LDS reservation (unused by the kernel) caps residency at 10 one-wave workgroups per
+    // compute unit for fp32 gradients (12 loads per lane) and 5 for fp16 (20 loads per lane).
+    // fp32: every stream is touched once per lane -> all non-temporal.  fp16: a lane's two
+    // state vectors share cache lines with its neighbours', so state loads stay cacheable.
+    const int lds_auto = f16 ? 32768 : 16384;
+    a.lds_reserve = (unsigned)(g_tuning.reduce_lds_reserve < 0 ? lds_auto : g_tuning.reduce_lds_reserve);
+    const int ntl = g_tuning.nt_loads < 0 ? 1 : g_tuning.nt_loads;
+    const int nts = g_tuning.nt_stores < 0 ? 1 : g_tuning.nt_stores;
+    const int ntx = g_tuning.nt_state_loads < 0 ? (f16 ? 0 : 1) : g_tuning.nt_state_loads;
+    const int nt = (ntl ? 1 : 0) | (nts ? 2 : 0) | (ntx ? 4 : 0);
 
     switch (W) {
-    case 1: launch_w<1>(a, f16, detect, ntl, nts); break;
-    case 2: launch_w<2>(a, f16, detect, ntl, nts); break;
-    case 4: launch_w<4>(a, f16, detect, ntl, nts); break;
-    case 8: launch_w<8>(a, f16, detect, ntl, nts); break;
-    case 16: launch_w<16>(a, f16, detect, ntl, nts); break;
+    case 1: launch_w<1>(a, f16, detect, nt); break;
+    case 2: launch_w<2>(a, f16, detect, nt); break;
+    case 4: launch_w<4>(a, f16, detect, nt); break;
+    case 8: launch_w<8>(a, f16, detect, nt); break;
+    case 16: launch_w<16>(a, f16, detect, nt); break;
     default:
         if (f16) { if (detect) launch_anyw<true, true>(a, W); else launch_anyw<true, false>(a, W); }
         else     { if (detect) launch_anyw<false, true>(a, W); else launch_anyw<false, false>(a, W); }

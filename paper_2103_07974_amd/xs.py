@@ -33,6 +33,9 @@ TUNE_REDUCE_WG_PER_CU = 0
 TUNE_COPY_WG_PER_CU = 1
 TUNE_NT_LOADS = 2
 TUNE_NT_STORES = 3
+TUNE_NT_STATE_LOADS = 4
+TUNE_REDUCE_LDS_RESERVE = 5
+N_TUNING_KEYS = 6
 
 EXPORTS = [
     "xs_status_string", "xs_last_error", "xs_bucket_layout", "xs_plan_create", "xs_plan_destroy",

@@ -124,3 +124,6 @@ def test_tuning_roundtrip_and_range():
         xs.tuning_set(xs.TUNE_REDUCE_WG_PER_CU, 1000)
     with pytest.raises(xs.XsError):
         xs.tuning_set(99, 1)
+    assert xs.tuning_get(xs.TUNE_REDUCE_LDS_RESERVE) == -1      # per-dtype default
+    with pytest.raises(xs.XsError):
+        xs.tuning_set(xs.TUNE_NT_LOADS, 2)

@@ -72,7 +72,7 @@ def _run(reps, x, v, inv=1.0, out_of_place=False, flag=None, n=None):
 
 
 # sizes: empty tail, pure tail, one vector, ragged, several workgroups, more than one
-# grid-stride trip at the default launch shape (256 CUs x 8 workgroups x 256 lanes x 4)
+# grid-stride trip at a capped launch shape (see test_launch_shapes_give_identical_results)
 SIZES = [1, 3, 4, 5, 7, 8, 9, 1023, 1024, 1025, 100003, 2 * 1024 * 1024 + 5, 9 * 1024 * 1024 + 3]
 
 
@@ -106,14 +106,16 @@ def test_any_W(W, dtype):
             assert _ulp_distance(gx, x32) == 0 and _ulp_distance(gv, v32) == 0
 
 
-@pytest.mark.parametrize("wg_per_cu", [0, 1, 8, 16])
-@pytest.mark.parametrize("nt_loads,nt_stores", [(0, 0), (1, 0), (1, 1)])
-def test_launch_shapes_give_identical_results(wg_per_cu, nt_loads, nt_stores):
-    old = [xs.tuning_get(k) for k in range(4)]
+@pytest.mark.parametrize("wg_per_cu,lds", [(0, 8192), (0, 0), (1, 0), (8, 8192), (32, 16384)])
+@pytest.mark.parametrize("nt_loads,nt_stores,nt_state", [(0, 0, 0), (1, 0, 0), (1, 1, 1), (0, 1, 1)])
+def test_launch_shapes_give_identical_results(wg_per_cu, lds, nt_loads, nt_stores, nt_state):
+    old = [xs.tuning_get(k) for k in range(xs.N_TUNING_KEYS)]
     try:
         xs.tuning_set(xs.TUNE_REDUCE_WG_PER_CU, wg_per_cu)
+        xs.tuning_set(xs.TUNE_REDUCE_LDS_RESERVE, lds)
         xs.tuning_set(xs.TUNE_NT_LOADS, nt_loads)
         xs.tuning_set(xs.TUNE_NT_STORES, nt_stores)
+        xs.tuning_set(xs.TUNE_NT_STATE_LOADS, nt_state)
         n = 3 * 1024 * 1024 + 1
         for dtype in (torch.float32, torch.float16):
             reps, x, v = _make(n, 8, dtype, seed=3000)
