@@ -22,6 +22,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the fused reduce + SGD kernel on the headline workload, from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a plain copy's reading of the same
+# counters (profiles/hbm_traffic_pmc_reduce_sgd_pack_unpack.md)
+MEASURED_TRAFFIC_BYTES = 1226779955
 
 
 def _median(xs_):
@@ -217,6 +221,37 @@ def cpu_baseline(w, align, budget_s=20.0):
                       f"{len(os.sched_getaffinity(0))} host cores available"}
 
 
+def traffic_probe():
+    """A few launches for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: a plain device copy
+    of known size first (its counter reading calibrates the unit), then the path's kernels
+    on the headline workload."""
+    import torch
+    from paper_2103_07974_amd import harness, workloads as wl, xs
+    xs.lib()
+    torch.cuda.set_device(0)
+    n = 256 * 1024 * 1024                       # 1 GiB read + 1 GiB written per copy
+    src = torch.empty(n, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    for w in (wl.RESNET50, wl.VGG16):
+        task = harness.make_task(w, "cuda")
+        for _ in range(3):
+            for r in range(w.W):
+                xs.fuse_pack(task.gplan, task.grad_tables[r], task.buckets[r])
+            xs.fused_reduce_sgd(task.buckets, task.n_bucket, task.params, task.momentum,
+                                w.lr, w.momentum, w.weight_decay, 1.0)
+            xs.fuse_unpack(task.pplan, task.params, task.param_table)
+        torch.cuda.synchronize()
+        print(json.dumps({"workload": w.name, "copy_bytes_each_way": n * 4,
+                          "reduce_bytes": task.reduce_bytes(), "pack_bytes": task.pack_bytes(),
+                          "unpack_bytes": task.unpack_bytes(), "bucket_elems": task.n_bucket}))
+        del task
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -224,7 +259,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=6)
     ap.add_argument("--quick", action="store_true", help="headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="launch a calibration copy and the path's kernels a few times (for rocprofv3 --pmc)")
     args = ap.parse_args()
+    if args.traffic_probe:
+        return traffic_probe()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the W workers' gradients are resident "
               "on that GPU); --gpus must be 1", file=sys.stderr)
@@ -259,7 +298,7 @@ def main():
                    "bytes_per_step_counted": reduce_bytes},
         "roofline": {"bound": "hbm", "kernel": "xs::reduce_sgd_kernel<8, false, false, true, true, true>",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
                      "bytes_per_launch": reduce_bytes, "avg_launch_ms": k_avg,
                      "median_launch_ms": _median(kernel_ms), "min_launch_ms": min(kernel_ms)},
     }
