@@ -146,6 +146,31 @@ int xs_fused_reduce_sgd(const void *const *replica_buckets, uint32_t W, int grad
                         const xs_sgd_hparams *hp, int32_t *found_inf, void *hip_stream);
 
 /* ------------------------------------------------------------------------
+ * The same pass without materialised buckets (Section 2.1 fuses the tensors only
+ * because the fused tensor has to be sent; on one GPU the layout alone suffices):
+ * element j of the bucket layout of gradient_plan is read from worker w's tensor
+ * that covers j, padding contributes +0, and the result is bit-identical to
+ * xs_fuse_pack x W + xs_fused_reduce_sgd (+ xs_fuse_unpack).
+ *   grad_ptrs          device array of n_tensors*W device pointers, laid out
+ *                      [tensor][worker]; element-aligned tensors of the plan's dtype
+ *   params, momentum, params_out, momentum_out, hp, found_inf   as in
+ *                      xs_fused_reduce_sgd, bucket layout, xs_plan_bucket_elems() long
+ *   param_tensor_ptrs  device array of n_tensors device pointers to fp32 per-layer
+ *                      parameter tensors, or NULL.  If given, the updated parameters
+ *                      are also written there in the same pass (no separate unpack).
+ *                      XS_ERR_UNSUPPORTED together with in-kernel overflow detection
+ *                      (out-of-place outputs and found_inf both given).
+ * No xs_fuse_pack runs in this form, so nothing raises found_inf before an in-place
+ * pass; mixed-precision callers use the out-of-place form and commit by swapping
+ * pointers when the flag is still zero.
+ */
+int xs_fused_gather_reduce_sgd(const xs_plan *gradient_plan, const void *const *grad_ptrs,
+                               uint32_t W, float *params, float *momentum,
+                               float *params_out, float *momentum_out,
+                               void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
+                               int32_t *found_inf, void *hip_stream);
+
+/* ------------------------------------------------------------------------
  * Training task ("distributed task i" of Algorithm 1) as seen by the scheduler.
  * All pointers in the descriptor are copied or referenced as stated and must
  * stay valid until xs_app_destroy.
@@ -206,6 +231,10 @@ int xs_app_wait_sync(xs_app *app, void *hip_stream);
  *      5 = bytes of LDS reserved per reduce workgroup; the kernel does not use LDS,
  *          the reservation only caps how many wavefronts share a compute unit.
  *      Keys 2-5 also accept -1 (the default): chosen per gradient dtype.
+ *      6 = absolute cap on reduce workgroups, 7 = on pack/unpack workgroups (0 = none):
+ *          paces a synchronisation that runs beside another task's computation.
+ *      8 = non-temporal loads and stores in pack/unpack (0/1).
+ *      9 = as 5, for xs_fused_gather_reduce_sgd (-1 = per dtype).
  * Returns XS_ERR_INVALID_ARG for an unknown key or out-of-range value.
  */
 int xs_tuning_set(int key, int value);

@@ -44,7 +44,9 @@ int compute_units()
 
 // -1 = chosen per gradient dtype at launch (see launch_reduce_sgd)
 Tuning g_tuning = {/*reduce_wg_per_cu*/ 0, /*copy_wg_per_cu*/ 8, /*nt_loads*/ -1, /*nt_stores*/ -1,
-                   /*nt_state_loads*/ -1, /*reduce_lds_reserve*/ -1};
+                   /*nt_state_loads*/ -1, /*reduce_lds_reserve*/ -1,
+                   /*reduce_max_wg*/ 0, /*copy_max_wg*/ 0, /*copy_nt*/ 1,
+                   /*gather_lds_reserve*/ -1};
 
 }  // namespace xs
 
@@ -76,6 +78,10 @@ extern "C" int xs_tuning_set(int key, int value)
     case 3: if (value < -1 || value > 1) break; g_tuning.nt_stores = value; return XS_OK;
     case 4: if (value < -1 || value > 1) break; g_tuning.nt_state_loads = value; return XS_OK;
     case 5: if (value < -1 || value > 65536) break; g_tuning.reduce_lds_reserve = value; return XS_OK;
+    case 6: if (value < 0) break; g_tuning.reduce_max_wg = value; return XS_OK;
+    case 7: if (value < 0) break; g_tuning.copy_max_wg = value; return XS_OK;
+    case 8: if (value < 0 || value > 1) break; g_tuning.copy_nt = value; return XS_OK;
+    case 9: if (value < -1 || value > 65536) break; g_tuning.gather_lds_reserve = value; return XS_OK;
     default: return fail(XS_ERR_INVALID_ARG, "xs_tuning_set: unknown key %d", key);
     }
     return fail(XS_ERR_INVALID_ARG, "xs_tuning_set: value %d out of range for key %d", value, key);
@@ -91,6 +97,10 @@ extern "C" int xs_tuning_get(int key, int *value_out)
     case 3: *value_out = g_tuning.nt_stores; return XS_OK;
     case 4: *value_out = g_tuning.nt_state_loads; return XS_OK;
     case 5: *value_out = g_tuning.reduce_lds_reserve; return XS_OK;
+    case 6: *value_out = g_tuning.reduce_max_wg; return XS_OK;
+    case 7: *value_out = g_tuning.copy_max_wg; return XS_OK;
+    case 8: *value_out = g_tuning.copy_nt; return XS_OK;
+    case 9: *value_out = g_tuning.gather_lds_reserve; return XS_OK;
     default: return fail(XS_ERR_INVALID_ARG, "xs_tuning_get: unknown key %d", key);
     }
 }
@@ -162,14 +172,31 @@ extern "C" int xs_plan_create(const uint64_t *numel, const uint64_t *offsets, ui
     p->n_chunks = (uint32_t)chunks;
     p->dev_blob = nullptr;
 
-    // one device blob: offsets | numel | chunk_prefix
+    // rows of kRowBytes of this dtype: which tensor's segment holds each row's first element
+    const uint64_t row_elems = kRowBytes / (uint64_t)es;
+    const uint64_t n_rows = (offsets[n_tensors] + row_elems - 1) / row_elems;
+    if (n_rows > 0x7fffffffull) { delete p; return fail(XS_ERR_SIZE, "xs_plan_create: bucket too large"); }
+    p->n_rows = n_rows;
+    std::vector<uint32_t> row_first((size_t)n_rows, 0);
+    {
+        uint32_t t = 0;
+        for (uint64_t r = 0; r < n_rows; ++r) {
+            const uint64_t j = r * row_elems;
+            while (t + 1 < n_tensors && offsets[t + 1] <= j) ++t;
+            row_first[(size_t)r] = t;
+        }
+    }
+
+    // one device blob: offsets | numel | chunk_prefix | row_first
     const size_t off_bytes = (size_t)(n_tensors + 1) * 8;
     const size_t num_bytes = (size_t)n_tensors * 8;
     const size_t pre_bytes = (size_t)(n_tensors + 1) * 4;
-    std::vector<unsigned char> host(off_bytes + num_bytes + pre_bytes);
+    const size_t row_bytes = (size_t)n_rows * 4;
+    std::vector<unsigned char> host(off_bytes + num_bytes + pre_bytes + row_bytes);
     memcpy(host.data(), offsets, off_bytes);
     if (n_tensors) memcpy(host.data() + off_bytes, numel, num_bytes);
     memcpy(host.data() + off_bytes + num_bytes, prefix.data(), pre_bytes);
+    if (n_rows) memcpy(host.data() + off_bytes + num_bytes + pre_bytes, row_first.data(), row_bytes);
     hipError_t e = hipMalloc(&p->dev_blob, host.size());
     if (e != hipSuccess) {
         delete p;
@@ -186,6 +213,7 @@ extern "C" int xs_plan_create(const uint64_t *numel, const uint64_t *offsets, ui
     p->tables.offsets = (const uint64_t *)d;
     p->tables.numel = (const uint64_t *)(d + off_bytes);
     p->tables.chunk_prefix = (const uint32_t *)(d + off_bytes + num_bytes);
+    p->tables.row_first = (const uint32_t *)(d + off_bytes + num_bytes + pre_bytes);
     *out = p;
     return XS_OK;
 }
@@ -290,4 +318,48 @@ extern "C" int xs_fused_reduce_sgd(const void *const *replica_buckets, uint32_t 
                              out_of_place ? momentum_out : momentum, *hp, found_inf,
                              /*detect=*/out_of_place && found_inf != nullptr,
                              (hipStream_t)hip_stream);
+}
+
+// ---- the same pass reading the per-layer gradient tensors directly ----------------------
+extern "C" int xs_fused_gather_reduce_sgd(const xs_plan *gradient_plan, const void *const *grad_ptrs,
+                                          uint32_t W, float *params, float *momentum,
+                                          float *params_out, float *momentum_out,
+                                          void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
+                                          int32_t *found_inf, void *hip_stream)
+{
+    if (!gradient_plan || gradient_plan->magic != XS_PLAN_MAGIC)
+        return fail(XS_ERR_INVALID_ARG, "xs_fused_gather_reduce_sgd: plan is NULL or not a plan");
+    if (W == 0 || W > XS_MAX_REPLICAS)
+        return fail(XS_ERR_INVALID_ARG, "xs_fused_gather_reduce_sgd: W = %u outside [1, %d]", W, XS_MAX_REPLICAS);
+    if (!hp) return fail(XS_ERR_INVALID_ARG, "xs_fused_gather_reduce_sgd: hp is NULL");
+    if ((params_out == nullptr) != (momentum_out == nullptr))
+        return fail(XS_ERR_INVALID_ARG,
+                    "xs_fused_gather_reduce_sgd: params_out and momentum_out must both be NULL or both be given");
+    const uint64_t n = gradient_plan->bucket_elems;
+    if (n == 0) return XS_OK;
+    if (!grad_ptrs || !params || !momentum)
+        return fail(XS_ERR_INVALID_ARG, "xs_fused_gather_reduce_sgd: grad_ptrs/params/momentum is NULL");
+    const bool out_of_place = params_out != nullptr;
+    if (!aligned16(params) || !aligned16(momentum) ||
+        (out_of_place && (!aligned16(params_out) || !aligned16(momentum_out))))
+        return fail(XS_ERR_ALIGNMENT,
+                    "xs_fused_gather_reduce_sgd: params/momentum pointers must be 16-byte aligned");
+    if (found_inf && ((uintptr_t)found_inf & 3u))
+        return fail(XS_ERR_ALIGNMENT, "xs_fused_gather_reduce_sgd: found_inf is not 4-byte aligned");
+    const bool detect = out_of_place && found_inf != nullptr;
+    if (detect && param_tensor_ptrs)
+        return fail(XS_ERR_UNSUPPORTED,
+                    "xs_fused_gather_reduce_sgd: parameter views cannot be written in a pass that is "
+                    "still deciding whether the step is skipped");
+    const uint64_t sbytes = n * 4;
+    const void *state[4] = {params, momentum, params_out, momentum_out};
+    const int n_state = out_of_place ? 4 : 2;
+    for (int a = 0; a < n_state; ++a)
+        for (int b = a + 1; b < n_state; ++b)
+            if (overlaps(state[a], sbytes, state[b], sbytes))
+                return fail(XS_ERR_INVALID_ARG, "xs_fused_gather_reduce_sgd: params/momentum buffers overlap");
+    return launch_gather_reduce_sgd(gradient_plan, grad_ptrs, W, params, momentum,
+                                    out_of_place ? params_out : params,
+                                    out_of_place ? momentum_out : momentum, param_tensor_ptrs, *hp,
+                                    found_inf, detect, (hipStream_t)hip_stream);
 }

@@ -30,6 +30,41 @@ struct __attribute__((packed, aligned(ALIGN))) LooseVec {
     u32x4 v;
 };
 
+typedef __attribute__((address_space(1))) u32x4 gvec;
+
+// 16-byte accesses with or without the non-temporal hint.  The element-aligned ("loose")
+// forms go through a packed struct so that the compiler may assume only ES-byte alignment;
+// the non-temporal builtin needs a naturally typed pointer, so those forms move four dwords
+// (fp32) through it only when the hint is asked for and the address happens to be aligned.
+template <bool NT>
+__device__ __forceinline__ u32x4 load_vec(const gvec *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+template <bool NT>
+__device__ __forceinline__ void store_vec(gvec *p, u32x4 v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+template <bool NT, int ES>
+__device__ __forceinline__ u32x4 load_loose(const __attribute__((address_space(1))) LooseVec<ES> *p)
+{
+    if constexpr (NT) {
+        if (((uintptr_t)p & 15u) == 0) return __builtin_nontemporal_load((const gvec *)p);
+    }
+    return p->v;
+}
+template <bool NT, int ES>
+__device__ __forceinline__ void store_loose(__attribute__((address_space(1))) LooseVec<ES> *p, u32x4 v)
+{
+    if constexpr (NT) {
+        if (((uintptr_t)p & 15u) == 0) { __builtin_nontemporal_store(v, (gvec *)p); return; }
+    }
+    p->v = v;
+}
+
 constexpr int kTrips = (kChunkBytes / 16 + 1 + kCopyThreads - 1) / kCopyThreads;   // 5
 
 // first index in table[0..count) whose value is > key, minus one
@@ -68,7 +103,7 @@ struct Elem<2> { typedef uint16_t type; };
 
 // UNPACK = false: tensors -> bucket (padding zero-filled, optional overflow flag)
 // UNPACK = true : bucket -> tensors (padding skipped)
-template <bool UNPACK, bool DETECT, int ES, bool LDS_TABLE>
+template <bool UNPACK, bool DETECT, int ES, bool LDS_TABLE, bool NT>
 __global__ __launch_bounds__(kCopyThreads) void copy_kernel(
     PlanTables tb, uint32_t n_tensors, uint32_t n_chunks, const uintptr_t *tensor_ptrs,
     unsigned char *bucket, int32_t *found_inf)
@@ -114,8 +149,8 @@ __global__ __launch_bounds__(kCopyThreads) void copy_kernel(
             const int32_t lo = j * 16 - skew;                       // byte offset inside the chunk
             fast[u] = j < nvec && lo >= 0 && lo + 16 <= vlen;
             if (fast[u]) {
-                if constexpr (UNPACK) r[u] = *(const __attribute__((address_space(1))) u32x4 *)(b + lo);
-                else r[u] = ((const __attribute__((address_space(1))) LooseVec<ES> *)(q + lo))->v;
+                if constexpr (UNPACK) r[u] = load_vec<NT>((const gvec *)(b + lo));
+                else r[u] = load_loose<NT, ES>((const __attribute__((address_space(1))) LooseVec<ES> *)(q + lo));
             }
         }
 #pragma unroll
@@ -123,9 +158,9 @@ __global__ __launch_bounds__(kCopyThreads) void copy_kernel(
             const int32_t j = (int32_t)threadIdx.x + u * (int32_t)kCopyThreads;
             const int32_t lo = j * 16 - skew;
             if (fast[u]) {
-                if constexpr (UNPACK) ((__attribute__((address_space(1))) LooseVec<ES> *)(q + lo))->v = r[u];
+                if constexpr (UNPACK) store_loose<NT, ES>((__attribute__((address_space(1))) LooseVec<ES> *)(q + lo), r[u]);
                 else {
-                    *(__attribute__((address_space(1))) u32x4 *)(b + lo) = r[u];
+                    store_vec<NT>((gvec *)(b + lo), r[u]);
                     if constexpr (DETECT)
                         bad = bad || nonfinite_word<ES>(r[u][0]) || nonfinite_word<ES>(r[u][1]) ||
                               nonfinite_word<ES>(r[u][2]) || nonfinite_word<ES>(r[u][3]);
@@ -162,17 +197,20 @@ static int launch_copy(const xs_plan *plan, const void *tensor_ptrs, void *bucke
     const int cus = compute_units();
     if (cus < 0) return cus;
     uint32_t blocks = (uint32_t)cus * (uint32_t)g_tuning.copy_wg_per_cu;
+    if (g_tuning.copy_max_wg > 0 && blocks > (uint32_t)g_tuning.copy_max_wg)
+        blocks = (uint32_t)g_tuning.copy_max_wg;
     if (blocks > plan->n_chunks) blocks = plan->n_chunks;
     const bool lds = plan->n_tensors + 1 <= kLdsPrefixCap;
     const size_t lds_bytes = lds ? (size_t)(plan->n_tensors + 1) * 4 : 0;
-    if (lds)
-        hipLaunchKernelGGL((copy_kernel<UNPACK, DETECT, ES, true>), dim3(blocks), dim3(kCopyThreads),
-                           lds_bytes, stream, plan->tables, plan->n_tensors, plan->n_chunks,
-                           (const uintptr_t *)tensor_ptrs, (unsigned char *)bucket, found_inf);
-    else
-        hipLaunchKernelGGL((copy_kernel<UNPACK, DETECT, ES, false>), dim3(blocks), dim3(kCopyThreads),
-                           0, stream, plan->tables, plan->n_tensors, plan->n_chunks,
-                           (const uintptr_t *)tensor_ptrs, (unsigned char *)bucket, found_inf);
+    const bool nt = g_tuning.copy_nt != 0;
+    const dim3 grid(blocks), block(kCopyThreads);
+#define XS_COPY_LAUNCH(LDS, NT)                                                                   \
+    hipLaunchKernelGGL((copy_kernel<UNPACK, DETECT, ES, LDS, NT>), grid, block, (LDS) ? lds_bytes : 0, \
+                       stream, plan->tables, plan->n_tensors, plan->n_chunks,                     \
+                       (const uintptr_t *)tensor_ptrs, (unsigned char *)bucket, found_inf)
+    if (lds) { if (nt) XS_COPY_LAUNCH(true, true); else XS_COPY_LAUNCH(true, false); }
+    else     { if (nt) XS_COPY_LAUNCH(false, true); else XS_COPY_LAUNCH(false, false); }
+#undef XS_COPY_LAUNCH
     XS_HIP_TRY(hipGetLastError());
     return XS_OK;
 }

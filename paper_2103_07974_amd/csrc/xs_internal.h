@@ -32,6 +32,10 @@ struct Tuning {
     int nt_stores;
     int nt_state_loads;
     int reduce_lds_reserve;   // bytes of LDS reserved per reduce workgroup (occupancy throttle)
+    int reduce_max_wg;        // absolute cap on reduce workgroups (0 = none): background pacing
+    int copy_max_wg;          // absolute cap on pack/unpack workgroups (0 = none)
+    int copy_nt;              // non-temporal loads and stores in pack/unpack
+    int gather_lds_reserve;   // as reduce_lds_reserve, for the gathering form
 };
 extern Tuning g_tuning;
 
@@ -43,11 +47,15 @@ extern Tuning g_tuning;
 constexpr uint32_t kChunkBytes = 16384;
 constexpr uint32_t kCopyThreads = 256;
 constexpr uint32_t kLdsPrefixCap = 8192;   // table entries that fit the LDS copy
+// The gathering reduce kernel works on rows of kRowBytes of gradient data per replica
+// (one 16-byte vector per lane of a wavefront).
+constexpr uint32_t kRowBytes = 1024;
 
 struct PlanTables {            // device pointers
     const uint64_t *offsets;   // n_tensors + 1
     const uint64_t *numel;     // n_tensors
     const uint32_t *chunk_prefix;  // n_tensors + 1
+    const uint32_t *row_first;     // n_rows: tensor whose segment holds the row's first element
 };
 
 }  // namespace xs
@@ -59,7 +67,8 @@ struct xs_plan {
     uint32_t elem_size;
     uint64_t bucket_elems;
     uint32_t n_chunks;
-    void *dev_blob;            // one allocation holding the three tables
+    uint64_t n_rows;
+    void *dev_blob;            // one allocation holding the tables
     xs::PlanTables tables;
 };
 
@@ -72,6 +81,10 @@ int launch_pack(const xs_plan *plan, const void *const *tensor_ptrs, void *bucke
                 int32_t *found_inf, hipStream_t stream);
 int launch_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,
                   hipStream_t stream);
+int launch_gather_reduce_sgd(const xs_plan *plan, const void *const *grad_ptrs, uint32_t W,
+                             const float *x_in, const float *v_in, float *x_out, float *v_out,
+                             void *const *param_ptrs, const xs_sgd_hparams &hp,
+                             int32_t *found_inf, bool detect, hipStream_t stream);
 int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64_t n,
                       const float *x_in, const float *v_in, float *x_out, float *v_out,
                       const xs_sgd_hparams &hp, int32_t *found_inf, bool detect,

@@ -320,6 +320,8 @@ int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64
         const uint64_t cap = (uint64_t)cus * (uint64_t)g_tuning.reduce_wg_per_cu;
         if (blocks > cap) blocks = cap;
     }
+    if (g_tuning.reduce_max_wg > 0 && blocks > (uint64_t)g_tuning.reduce_max_wg)
+        blocks = (uint64_t)g_tuning.reduce_max_wg;
     if (blocks > 0x7fffffffull) blocks = 0x7fffffffull;   // the loop covers the rest
 
     LaunchArgs a;

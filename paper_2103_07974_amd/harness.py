@@ -28,6 +28,7 @@ class TaskState:
     params: torch.Tensor                     # fp32 bucket
     momentum: torch.Tensor                   # fp32 bucket
     found_inf: torch.Tensor                  # int32[1]
+    gather_table: torch.Tensor               # [T][W] device pointer table for the gathering form
 
     @property
     def n_bucket(self) -> int:
@@ -44,6 +45,11 @@ class TaskState:
 
     def unpack_bytes(self) -> int:
         return 2 * 4 * self.workload.n_elems
+
+    def gather_bytes(self, views: bool = True) -> int:
+        """Algorithmic bytes of the gathering form: as reduce_bytes, plus the per-tensor
+        parameter views written when the unpack is fused in."""
+        return self.reduce_bytes() + (4 * self.workload.n_elems if views else 0)
 
     def make_app(self, compute: Optional[Callable[[int], None]] = None,
                  use_found_inf: bool = False) -> xs.App:
@@ -79,6 +85,7 @@ def make_task(w: wl.Workload, device="cuda", align: int = DEFAULT_ALIGN,
     xs.fuse_pack(pplan, param_table, params)            # parameters enter the bucket layout
     momentum = torch.zeros(n_bucket, dtype=torch.float32, device=dev)
     found_inf = torch.zeros(1, dtype=torch.int32, device=dev)
+    gather_table = xs.gather_pointer_table(grads, dev)
     torch.cuda.synchronize(dev)
     return TaskState(w, align, offsets, gplan, pplan, grads, grad_tables, buckets, param_tensors,
-                     param_table, params, momentum, found_inf)
+                     param_table, params, momentum, found_inf, gather_table)

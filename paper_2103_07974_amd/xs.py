@@ -35,12 +35,16 @@ TUNE_NT_LOADS = 2
 TUNE_NT_STORES = 3
 TUNE_NT_STATE_LOADS = 4
 TUNE_REDUCE_LDS_RESERVE = 5
-N_TUNING_KEYS = 6
+TUNE_REDUCE_MAX_WG = 6
+TUNE_COPY_MAX_WG = 7
+TUNE_COPY_NT = 8
+TUNE_GATHER_LDS_RESERVE = 9
+N_TUNING_KEYS = 10
 
 EXPORTS = [
     "xs_status_string", "xs_last_error", "xs_bucket_layout", "xs_plan_create", "xs_plan_destroy",
     "xs_plan_bucket_elems", "xs_plan_n_tensors", "xs_fuse_pack", "xs_fuse_unpack",
-    "xs_fused_reduce_sgd", "xs_app_create", "xs_app_destroy", "xs_app_sync", "xs_crossover_step",
+    "xs_fused_reduce_sgd", "xs_fused_gather_reduce_sgd", "xs_app_create", "xs_app_destroy", "xs_app_sync", "xs_crossover_step",
     "xs_crossover_drain", "xs_app_wait_sync", "xs_tuning_set", "xs_tuning_get",
 ]
 
@@ -96,6 +100,8 @@ def lib() -> ctypes.CDLL:
     L.xs_fused_reduce_sgd.argtypes = [ctypes.POINTER(vp), ctypes.c_uint32, ctypes.c_int,
                                       ctypes.c_uint64, vp, vp, vp, vp,
                                       ctypes.POINTER(SgdHparams), vp, vp]
+    L.xs_fused_gather_reduce_sgd.argtypes = [vp, vp, ctypes.c_uint32, vp, vp, vp, vp, vp,
+                                             ctypes.POINTER(SgdHparams), vp, vp]
     L.xs_app_create.argtypes = [ctypes.POINTER(AppDesc), ctypes.POINTER(vp)]
     L.xs_app_destroy.argtypes = [vp]
     L.xs_app_sync.argtypes = [vp, vp]
@@ -227,6 +233,32 @@ def fused_reduce_sgd(replica_buckets: Sequence[torch.Tensor], n_elems: int, para
                                      _dptr(momentum), _dptr(params_out), _dptr(momentum_out),
                                      ctypes.byref(hp), _dptr(found_inf), _stream_ptr(stream)),
            "xs_fused_reduce_sgd")
+
+
+def gather_pointer_table(grads: Sequence[Sequence[torch.Tensor]], device=None) -> torch.Tensor:
+    """Device array [tensor][worker] of gradient tensor addresses for the gathering form.
+    grads[w][t] is worker w's tensor t."""
+    W = len(grads)
+    T = len(grads[0]) if W else 0
+    if device is None:
+        device = grads[0][0].device if W and T else torch.device("cuda")
+    ptrs = [grads[w][t].data_ptr() for t in range(T) for w in range(W)]
+    return torch.tensor(ptrs if ptrs else [0], dtype=torch.int64).to(device)
+
+
+def fused_gather_reduce_sgd(plan: Plan, grad_ptrs: torch.Tensor, W: int, params: torch.Tensor,
+                            momentum: torch.Tensor, lr: float, mu: float, wd: float,
+                            inv_loss_scale: float = 1.0,
+                            params_out: Optional[torch.Tensor] = None,
+                            momentum_out: Optional[torch.Tensor] = None,
+                            param_tensor_ptrs: Optional[torch.Tensor] = None,
+                            found_inf: Optional[torch.Tensor] = None, stream=None) -> None:
+    hp = SgdHparams(lr, mu, wd, inv_loss_scale)
+    _check(lib().xs_fused_gather_reduce_sgd(plan.handle, _dptr(grad_ptrs), int(W), _dptr(params),
+                                            _dptr(momentum), _dptr(params_out), _dptr(momentum_out),
+                                            _dptr(param_tensor_ptrs), ctypes.byref(hp),
+                                            _dptr(found_inf), _stream_ptr(stream)),
+           "xs_fused_gather_reduce_sgd")
 
 
 # ---------------------------------------------------------------- crossover
