@@ -100,22 +100,67 @@ def time_kernels(task, stream, reps=30, warm=5):
     return out
 
 
-def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192):
-    """Two tasks alternate as in Algorithm 1: one computes (a chain of bf16 GEMMs standing in
-    for forward + backward) while the other synchronises on the second stream."""
+def time_gather(tasks, stream, reps=30, warm=6):
+    """The gathering form (no buckets, parameter views written in the same pass): one kernel
+    is the whole step.  Rotates over the buffer sets like the timed region."""
+    import torch
+    from paper_2103_07974_amd import xs
+    ts = []
+    with torch.cuda.stream(stream):
+        for i in range(warm + reps):
+            t = tasks[i % len(tasks)]; w = t.workload
+            a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            xs.fused_gather_reduce_sgd(t.gplan, t.gather_table, w.W, t.params, t.momentum, w.lr,
+                                       w.momentum, w.weight_decay, 1.0 / w.loss_scale,
+                                       param_tensor_ptrs=t.param_table, stream=stream)
+            b.record(stream); b.synchronize()
+            if i >= warm:
+                ts.append(a.elapsed_time(b))
+    ms = _median(ts)
+    return {"step_ms": ms, "min_ms": min(ts),
+            "GBs_moved": tasks[0].gather_bytes(True) / ms / 1e6,
+            "frac_of_hbm_peak": tasks[0].gather_bytes(True) / ms / 1e6 / HBM_PEAK_GBS,
+            "GBs_by_headline_formula": tasks[0].reduce_bytes() / ms / 1e6}
+
+
+def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False, standin="gemm",
+                   cross_only=False):
+    """Two tasks alternate as in Algorithm 1: one computes (a stand-in for forward + backward)
+    while the other synchronises on the second stream.
+
+    standin="gemm": the configured chain of bf16 GEMMs.  standin="alu": a chain of elementwise
+    lgamma passes over 16M fp32 values - arithmetic-bound kernels of ordinary occupancy, the
+    kind of kernel a synchronisation wave can share a compute unit with."""
     import torch
     from paper_2103_07974_amd import xs
     g = torch.Generator(device="cuda"); g.manual_seed(task_a.workload.seed + 100)
-    B = (torch.randn(dim, dim, generator=g, device="cuda") / dim ** 0.5).to(torch.bfloat16)
-    Y = [torch.randn(dim, dim, generator=g, device="cuda").to(torch.bfloat16) for _ in range(2)]
+    if standin == "gemm":
+        B = (torch.randn(dim, dim, generator=g, device="cuda") / dim ** 0.5).to(torch.bfloat16)
+        Y = [torch.randn(dim, dim, generator=g, device="cuda").to(torch.bfloat16) for _ in range(2)]
 
-    def compute(stream_ptr):
-        s = torch.cuda.ExternalStream(stream_ptr)
-        with torch.cuda.stream(s):
-            for k in range(chain):
-                torch.matmul(Y[k & 1], B, out=Y[1 - (k & 1)])
+        def compute(stream_ptr):
+            s = torch.cuda.ExternalStream(stream_ptr)
+            with torch.cuda.stream(s):
+                for k in range(chain):
+                    torch.matmul(Y[k & 1], B, out=Y[1 - (k & 1)])
+        label = f"{chain}x[{dim}x{dim}]@[{dim}x{dim}] bf16"
+    else:
+        # arithmetic only: one kernel of 256 workgroups of 256 lanes (one per compute unit, a
+        # quarter of the wave slots, few registers, no memory traffic); iteration count
+        # calibrated so that it lasts as long as the GEMM chain does
+        sink = torch.zeros(256, device="cuda")
+        target_ms, probe_iters = 12.6, 100000
+        a0 = torch.cuda.Event(enable_timing=True); a1 = torch.cuda.Event(enable_timing=True)
+        xs.standin_alu(256, probe_iters, sink); torch.cuda.synchronize()
+        a0.record(); xs.standin_alu(256, probe_iters, sink); a1.record(); a1.synchronize()
+        iters = max(1000, int(probe_iters * target_ms / a0.elapsed_time(a1)))
 
-    apps = [task_a.make_app(compute), task_b.make_app(compute)]
+        def compute(stream_ptr):
+            xs.standin_alu(256, iters, sink, stream_ptr)
+        label = f"one arithmetic-only kernel, 256x256 lanes, {iters} x 8 multiply-adds per lane"
+    apps = [task_a.make_app(compute, fused_gather=fused_gather),
+            task_b.make_app(compute, fused_gather=fused_gather)]
     cs, ss = torch.cuda.Stream(), torch.cuda.Stream()
 
     def run_cross(record=None):
@@ -162,6 +207,13 @@ def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / n
 
+    if cross_only:       # for kernel tracing: nothing but the two-stream schedule itself
+        run_cross()
+        ms = run_cross()
+        for a in apps:
+            a.destroy()
+        return {"T": T, "compute_standin": label, "t_cross_ms": ms,
+                "sync_kernels": "gather form" if fused_gather else "packs, reduce+SGD, unpack"}
     run_comp(); run_serial(); run_cross()                    # warm-up of every mode
     t_comp = _median([run_comp() for _ in range(3)])
     t_serial = _median([run_serial() for _ in range(3)])
@@ -177,7 +229,8 @@ def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192):
         if d > 0:
             exposed[who] += d; late[who] += 1
     res = {
-        "T": T, "gemm_chain": f"{chain}x[{dim}x{dim}]@[{dim}x{dim}] bf16",
+        "T": T, "compute_standin": label,
+        "sync_kernels": "gather+reduce+SGD+views (1 kernel)" if fused_gather else "8 packs, reduce+SGD, unpack",
         "t_comp_ms": t_comp, "t_serial_ms": t_serial, "t_cross_ms": t_cross,
         "sum_sync_ms": sum_sync, "sync_a_alone_ms": sync_a, "sync_b_alone_ms": sync_b,
         "compute_chain_ms": t_comp / (2 * T),
@@ -186,8 +239,8 @@ def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192):
         "speedup_vs_serial": t_serial / t_cross,
         "syncs_finished_before_compute_end": {"a": count[0] - late[0], "b": count[1] - late[1],
                                               "of_a": count[0], "of_b": count[1]},
-        "hidden_b_by_events": 1.0 - exposed[1] / (count[1] * sync_b) if count[1] else None,
-        "hidden_a_by_events": 1.0 - exposed[0] / (count[0] * sync_a) if count[0] else None,
+        "hidden_b_no_stall": 1.0 - exposed[1] / (count[1] * sync_b) if count[1] else None,
+        "hidden_a_no_stall": 1.0 - exposed[0] / (count[0] * sync_a) if count[0] else None,
     }
     for a in apps:
         a.destroy()
@@ -259,6 +312,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=6)
     ap.add_argument("--quick", action="store_true", help="headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--crossover-only", action="store_true",
+                    help="run only the crossover pair (T outer iterations), for rocprofv3 --kernel-trace")
+    ap.add_argument("--T", type=int, default=20)
+    ap.add_argument("--gather", action="store_true", help="with --crossover-only: gathering form")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="launch a calibration copy and the path's kernels a few times (for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -274,6 +331,12 @@ def main():
     xs.lib()
     torch.cuda.set_device(0)
     stream = torch.cuda.Stream()
+
+    if args.crossover_only:
+        ta = harness.make_task(wl.RESNET50, "cuda")
+        tb = harness.make_task(wl.VGG16, "cuda")
+        print(json.dumps(crossover_pair(ta, tb, T=args.T, fused_gather=args.gather, cross_only=True)))
+        return 0
 
     w = wl.RESNET50
     tasks = [harness.make_task(w, "cuda") for _ in range(3)]
@@ -303,6 +366,7 @@ def main():
                      "median_launch_ms": _median(kernel_ms), "min_launch_ms": min(kernel_ms)},
     }
     extra = {"resnet50": time_kernels(tasks[0], stream)}
+    extra["resnet50"]["gather_form"] = time_gather(tasks, stream)
     del tasks
     torch.cuda.empty_cache()
 
@@ -336,12 +400,16 @@ def main():
             torch.cuda.synchronize()
             extra["vgg16"]["step_ms"] = (time.perf_counter() - t0) * 1e3 / 10
             app.destroy()
+        extra["vgg16"]["gather_form"] = time_gather([tb], stream, reps=15, warm=3)
         extra["crossover"] = crossover_pair(ta, tb)
+        extra["crossover_gather_form"] = crossover_pair(ta, tb, fused_gather=True)
+        extra["crossover_alu_standin_gather_form"] = crossover_pair(ta, tb, fused_gather=True, standin="alu")
         del ta, tb
         torch.cuda.empty_cache()
 
-        bert = harness.make_task(wl.BERT_LARGE_F16, "cuda", shared_grads=True)
+        bert = harness.make_task(wl.BERT_LARGE_F16, "cuda")
         extra["bert_large_f16"] = time_kernels(bert, stream, reps=15, warm=3)
+        extra["bert_large_f16"]["gather_form"] = time_gather([bert], stream, reps=10, warm=2)
         del bert
         torch.cuda.empty_cache()
 

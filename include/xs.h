@@ -193,7 +193,15 @@ typedef struct {
     int32_t *found_inf;                      /* device, may be NULL                   */
     xs_compute_fn compute;                   /* may be NULL (no compute enqueued)     */
     void *compute_ctx;
+    uint32_t flags;                          /* XS_APP_* bits                         */
+    const void *const *grad_ptrs_tw;         /* device [n_tensors][W] table; required
+                                                with XS_APP_FUSED_GATHER, else may be NULL */
 } xs_app_desc;
+
+/* Synchronise with xs_fused_gather_reduce_sgd (gradients read from the per-layer tensors,
+ * parameters written to the views in the same pass) instead of W packs + reduce + unpack.
+ * replica_buckets and grad_tensor_ptrs are then unused and may be NULL. */
+#define XS_APP_FUSED_GATHER 1u
 
 typedef struct xs_app xs_app;
 int xs_app_create(const xs_app_desc *desc, xs_app **out);   /* creates two HIP events */
@@ -219,6 +227,14 @@ int xs_crossover_drain(xs_app *app, void *sync_stream);
 
 /* Makes hip_stream wait for app's last enqueued synchronisation (no-op if none). */
 int xs_app_wait_sync(xs_app *app, void *hip_stream);
+
+/* ------------------------------------------------------------------------
+ * Arithmetic-only compute stand-in for overlap measurements (Section 2.1: one task
+ * computes while the other synchronises): `workgroups` workgroups of 256 lanes each run
+ * 8*iters dependent multiply-adds per lane and touch no memory.  sink: device, at least
+ * 256 floats, practically never written.  Enqueue only.
+ */
+int xs_standin_alu(uint32_t workgroups, uint32_t iters, float *sink, void *hip_stream);
 
 /* ------------------------------------------------------------------------
  * Launch tuning (process-wide; defaults are the measured best for MI355X).

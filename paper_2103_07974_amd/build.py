@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libxs.so")
 SOURCES = ["xs_api.hip", "xs_reduce_sgd.hip", "xs_gather_reduce_sgd.hip", "xs_copy.hip",
-           "xs_crossover.hip"]
+           "xs_crossover.hip", "xs_standin.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -1,7 +1,8 @@
 // Two-stream crossover driver (arXiv 2103.07974, Algorithm 1 and Section 2.1).
 //
 // A task's gradient computation runs on the compute stream; its synchronisation
-// (W packs, fused reduce + SGD, unpack) runs on the sync stream.  Two events per
+// (W packs, fused reduce + SGD, unpack; or the single gathering kernel when the task
+// was created with XS_APP_FUSED_GATHER) runs on the sync stream.  Two events per
 // task carry the only dependencies the algorithm has:
 //   grads_ready  recorded on the compute stream after the task's computation;
 //                the task's synchronisation waits for it ("Send ... for gradient
@@ -27,6 +28,8 @@ struct xs_app {
     float *params;
     float *momentum;
     void *const *param_table;
+    const void *const *gather_table;   // device [T][W], fused-gather mode
+    uint32_t flags;
     xs_sgd_hparams hp;
     int32_t *found_inf;
     xs_compute_fn compute;
@@ -57,13 +60,19 @@ extern "C" int xs_app_create(const xs_app_desc *d, xs_app **out)
     if (d->W == 0 || d->W > XS_MAX_REPLICAS)
         return fail(XS_ERR_INVALID_ARG, "xs_app_create: W = %u outside [1, %d]", d->W, XS_MAX_REPLICAS);
     const bool empty = d->gradient_plan->bucket_elems == 0;
-    if (!empty && (!d->grad_tensor_ptrs || !d->replica_buckets || !d->params || !d->momentum ||
-                   !d->param_tensor_ptrs))
+    if (d->flags & ~XS_APP_FUSED_GATHER)
+        return fail(XS_ERR_UNSUPPORTED, "xs_app_create: unknown flags 0x%x", d->flags);
+    const bool gather = (d->flags & XS_APP_FUSED_GATHER) != 0;
+    if (!empty && (!d->params || !d->momentum || !d->param_tensor_ptrs))
+        return fail(XS_ERR_INVALID_ARG, "xs_app_create: a required pointer is NULL");
+    if (!empty && gather && !d->grad_ptrs_tw)
+        return fail(XS_ERR_INVALID_ARG, "xs_app_create: XS_APP_FUSED_GATHER needs grad_ptrs_tw");
+    if (!empty && !gather && (!d->grad_tensor_ptrs || !d->replica_buckets))
         return fail(XS_ERR_INVALID_ARG, "xs_app_create: a required pointer is NULL");
     if (!empty) {
         if (!aligned16(d->params) || !aligned16(d->momentum))
             return fail(XS_ERR_ALIGNMENT, "xs_app_create: params/momentum must be 16-byte aligned");
-        for (uint32_t w = 0; w < d->W; ++w) {
+        for (uint32_t w = 0; !gather && w < d->W; ++w) {
             if (!d->grad_tensor_ptrs[w] || !d->replica_buckets[w])
                 return fail(XS_ERR_INVALID_ARG, "xs_app_create: worker %u has a NULL table or bucket", w);
             if (!aligned16(d->replica_buckets[w]))
@@ -76,10 +85,12 @@ extern "C" int xs_app_create(const xs_app_desc *d, xs_app **out)
     a->gplan = d->gradient_plan;
     a->pplan = d->parameter_plan;
     a->W = d->W;
-    if (!empty) {
+    if (!empty && !gather) {
         a->grad_tables.assign(d->grad_tensor_ptrs, d->grad_tensor_ptrs + d->W);
         a->buckets.assign(d->replica_buckets, d->replica_buckets + d->W);
     }
+    a->gather_table = d->grad_ptrs_tw;
+    a->flags = d->flags;
     a->params = d->params;
     a->momentum = d->momentum;
     a->param_table = d->param_tensor_ptrs;
@@ -119,6 +130,9 @@ extern "C" int xs_app_destroy(xs_app *a)
 static int enqueue_sync(xs_app *a, hipStream_t s)
 {
     if (a->gplan->bucket_elems == 0) return XS_OK;
+    if (a->flags & XS_APP_FUSED_GATHER)
+        return xs_fused_gather_reduce_sgd(a->gplan, a->gather_table, a->W, a->params, a->momentum,
+                                          nullptr, nullptr, a->param_table, &a->hp, a->found_inf, s);
     for (uint32_t w = 0; w < a->W; ++w) {
         int rc = xs_fuse_pack(a->gplan, a->grad_tables[w], a->buckets[w], a->found_inf, s);
         if (rc != XS_OK) return rc;

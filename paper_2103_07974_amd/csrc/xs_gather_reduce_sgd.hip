@@ -354,7 +354,9 @@ int launch_gather_reduce_sgd(const xs_plan *plan, const void *const *grad_ptrs, 
         blocks = (uint64_t)g_tuning.reduce_max_wg;
     if (blocks > 0x7fffffffull) blocks = 0x7fffffffull;
     const dim3 grid((unsigned)blocks);
-    const int lds_auto = f16 ? 32768 : 16384;
+    // the address look-ups in front of the loads want about twice the residency of the
+    // bucket form: 20 one-wave workgroups per compute unit for fp32, 10 for fp16 (measured)
+    const int lds_auto = f16 ? 16384 : 8192;
     const unsigned lds = (unsigned)(g_tuning.gather_lds_reserve < 0 ? lds_auto : g_tuning.gather_lds_reserve);
     const bool views = param_ptrs != nullptr;
 

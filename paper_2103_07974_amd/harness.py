@@ -52,11 +52,12 @@ class TaskState:
         return self.reduce_bytes() + (4 * self.workload.n_elems if views else 0)
 
     def make_app(self, compute: Optional[Callable[[int], None]] = None,
-                 use_found_inf: bool = False) -> xs.App:
+                 use_found_inf: bool = False, fused_gather: bool = False) -> xs.App:
         w = self.workload
         return xs.App(self.gplan, self.pplan, self.grad_tables, self.buckets, self.params,
                       self.momentum, self.param_table, w.lr, w.momentum, w.weight_decay,
-                      1.0 / w.loss_scale, self.found_inf if use_found_inf else None, compute)
+                      1.0 / w.loss_scale, self.found_inf if use_found_inf else None, compute,
+                      gather_table=self.gather_table if fused_gather else None, W=w.W)
 
 
 def make_task(w: wl.Workload, device="cuda", align: int = DEFAULT_ALIGN,

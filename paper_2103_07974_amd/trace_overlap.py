@@ -1,0 +1,73 @@
+"""Stream-overlap fraction from a rocprofv3 kernel trace (CSV).
+
+    python -m paper_2103_07974_amd.trace_overlap <prefix>_kernel_trace.csv
+
+For the crossover schedule (arXiv 2103.07974, Section 2.1) the question is how much of the
+time the synchronisation kernels run falls inside the time the other task's compute kernels
+run:  sum |sync interval ∩ union(compute intervals)| / sum |sync interval|.
+Kernels of this library (namespace xs::, except the compute stand-in) count as
+synchronisation; GEMM kernels (names starting with Cijk_) and the stand-in count as compute.
+Only the part of the trace where both kinds appear within one millisecond of each other is
+used, so that stand-alone timing loops in the same trace do not dilute the figure.
+"""
+from __future__ import annotations
+
+import csv
+import sys
+from typing import List, Tuple
+
+
+def classify(name: str) -> str | None:
+    if "standin_alu" in name or name.startswith("Cijk_"):
+        return "compute"
+    if "xs::" in name:
+        return "sync"
+    return None
+
+
+def merge(iv: List[Tuple[int, int]]) -> List[Tuple[int, int]]:
+    out: List[Tuple[int, int]] = []
+    for s, e in sorted(iv):
+        if out and s <= out[-1][1]:
+            out[-1] = (out[-1][0], max(out[-1][1], e))
+        else:
+            out.append((s, e))
+    return out
+
+
+def overlap_with(iv: Tuple[int, int], merged: List[Tuple[int, int]]) -> int:
+    s, e = iv
+    tot = 0
+    for a, b in merged:
+        if b <= s:
+            continue
+        if a >= e:
+            break
+        tot += min(e, b) - max(s, a)
+    return tot
+
+
+def analyse(path: str, slack_ns: int = 1_000_000):
+    sync, comp = [], []
+    for r in csv.DictReader(open(path)):
+        kind = classify(r["Kernel_Name"])
+        if kind is None:
+            continue
+        iv = (int(r["Start_Timestamp"]), int(r["End_Timestamp"]))
+        (sync if kind == "sync" else comp).append(iv)
+    comp_m = merge(comp)
+    # widen compute intervals by the slack to decide which sync kernels belong to the crossover phase
+    near = merge([(a - slack_ns, b + slack_ns) for a, b in comp_m])
+    used = [iv for iv in sync if overlap_with(iv, near) > 0]
+    tot = sum(e - s for s, e in used)
+    inside = sum(overlap_with(iv, comp_m) for iv in used)
+    return {"sync_kernels_in_crossover_phase": len(used), "sync_kernels_total": len(sync),
+            "sync_time_ms": tot / 1e6, "sync_time_inside_compute_ms": inside / 1e6,
+            "stream_overlap_fraction": inside / tot if tot else None}
+
+
+if __name__ == "__main__":
+    if len(sys.argv) != 2:
+        sys.exit(__doc__)
+    for k, v in analyse(sys.argv[1]).items():
+        print(f"{k}: {v}")

@@ -45,7 +45,7 @@ EXPORTS = [
     "xs_status_string", "xs_last_error", "xs_bucket_layout", "xs_plan_create", "xs_plan_destroy",
     "xs_plan_bucket_elems", "xs_plan_n_tensors", "xs_fuse_pack", "xs_fuse_unpack",
     "xs_fused_reduce_sgd", "xs_fused_gather_reduce_sgd", "xs_app_create", "xs_app_destroy", "xs_app_sync", "xs_crossover_step",
-    "xs_crossover_drain", "xs_app_wait_sync", "xs_tuning_set", "xs_tuning_get",
+    "xs_crossover_drain", "xs_app_wait_sync", "xs_tuning_set", "xs_tuning_get", "xs_standin_alu",
 ]
 
 
@@ -71,7 +71,11 @@ class AppDesc(ctypes.Structure):
                 ("params", ctypes.c_void_p), ("momentum", ctypes.c_void_p),
                 ("param_tensor_ptrs", ctypes.c_void_p),
                 ("hp", SgdHparams), ("found_inf", ctypes.c_void_p),
-                ("compute", COMPUTE_FN), ("compute_ctx", ctypes.c_void_p)]
+                ("compute", COMPUTE_FN), ("compute_ctx", ctypes.c_void_p),
+                ("flags", ctypes.c_uint32), ("grad_ptrs_tw", ctypes.c_void_p)]
+
+
+XS_APP_FUSED_GATHER = 1
 
 
 _lib = None
@@ -108,6 +112,7 @@ def lib() -> ctypes.CDLL:
     L.xs_crossover_step.argtypes = [vp, vp, vp, vp]
     L.xs_crossover_drain.argtypes = [vp, vp]
     L.xs_app_wait_sync.argtypes = [vp, vp]
+    L.xs_standin_alu.argtypes = [ctypes.c_uint32, ctypes.c_uint32, vp, vp]
     L.xs_tuning_set.argtypes = [ctypes.c_int, ctypes.c_int]
     L.xs_tuning_get.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
     for name in EXPORTS:
@@ -269,12 +274,15 @@ class App:
                  grad_tables: Sequence[torch.Tensor], replica_buckets: Sequence[torch.Tensor],
                  params: torch.Tensor, momentum: torch.Tensor, param_table: torch.Tensor,
                  lr: float, mu: float, wd: float, inv_loss_scale: float = 1.0,
-                 found_inf: Optional[torch.Tensor] = None, compute=None):
-        W = len(replica_buckets)
+                 found_inf: Optional[torch.Tensor] = None, compute=None,
+                 gather_table: Optional[torch.Tensor] = None, W: Optional[int] = None):
+        """With gather_table (device [tensor][worker] addresses) the app synchronises with the
+        gathering kernel; grad_tables and replica_buckets may then be empty and W must be given."""
+        W = len(replica_buckets) if W is None else W
         self._keep = (gradient_plan, parameter_plan, list(grad_tables), list(replica_buckets),
-                      params, momentum, param_table, found_inf)
-        self._tables = (ctypes.c_void_p * max(W, 1))(*[_dptr(t) for t in grad_tables])
-        self._buckets = (ctypes.c_void_p * max(W, 1))(*[_dptr(b) for b in replica_buckets])
+                      params, momentum, param_table, found_inf, gather_table)
+        self._tables = (ctypes.c_void_p * max(len(grad_tables), 1))(*[_dptr(t) for t in grad_tables])
+        self._buckets = (ctypes.c_void_p * max(len(replica_buckets), 1))(*[_dptr(b) for b in replica_buckets])
         if compute is not None:
             def _tramp(_ctx, stream_ptr, _fn=compute):
                 _fn(int(stream_ptr) if stream_ptr else 0)
@@ -294,6 +302,8 @@ class App:
         d.found_inf = _dptr(found_inf)
         d.compute = self._cb
         d.compute_ctx = None
+        d.flags = XS_APP_FUSED_GATHER if gather_table is not None else 0
+        d.grad_ptrs_tw = _dptr(gather_table)
         h = ctypes.c_void_p()
         _check(lib().xs_app_create(ctypes.byref(d), ctypes.byref(h)), "xs_app_create")
         self.handle = h
@@ -324,6 +334,11 @@ def crossover_step(compute_app: App, sync_app: Optional[App], compute_stream, sy
 
 def crossover_drain(app: App, sync_stream) -> None:
     _check(lib().xs_crossover_drain(app.handle, _stream_ptr(sync_stream)), "xs_crossover_drain")
+
+
+def standin_alu(workgroups: int, iters: int, sink: torch.Tensor, stream=None) -> None:
+    _check(lib().xs_standin_alu(int(workgroups), int(iters), _dptr(sink), _stream_ptr(stream)),
+           "xs_standin_alu")
 
 
 def tuning_set(key: int, value: int) -> None:

@@ -39,10 +39,11 @@ def _host_compute(params, W, t):
     return [[(p * _coef(w) + k).astype(np.float32) for p in params] for w in range(W)]
 
 
-def _run_gpu(workloads, T, align):
+def _run_gpu(workloads, T, align, fused_gather=False):
     tasks = [harness.make_task(w, "cuda", align) for w in workloads]
     counters = [[0] for _ in tasks]
-    apps = [t.make_app(_device_compute(t, c)) for t, c in zip(tasks, counters)]
+    apps = [t.make_app(_device_compute(t, c), fused_gather=fused_gather)
+            for t, c in zip(tasks, counters)]
     cs, ss = torch.cuda.Stream(), torch.cuda.Stream()
     N = len(apps)
     outstanding = set()
@@ -88,9 +89,10 @@ def _run_oracle(workloads, T, align, tasks):
 
 
 @pytest.mark.parametrize("T", [1, 4])
-def test_two_tasks_match_algorithm_1(T):
+@pytest.mark.parametrize("fused_gather", [False, True])
+def test_two_tasks_match_algorithm_1(T, fused_gather):
     wls = [_mini("a", [(300, 7), (64,), (5000,)], W=2), _mini("b", [(17,), (9000, 3)], W=4)]
-    tasks, apps, counters = _run_gpu(wls, T, align=8)
+    tasks, apps, counters = _run_gpu(wls, T, align=8, fused_gather=fused_gather)
     state, log = _run_oracle(wls, T, 8, tasks)
     assert [c[0] for c in counters] == [T, T]
     assert sum(1 for e in log if e[0] in ("update", "drain")) == 2 * T
