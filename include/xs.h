@@ -251,6 +251,8 @@ int xs_standin_alu(uint32_t workgroups, uint32_t iters, float *sink, void *hip_s
  *          paces a synchronisation that runs beside another task's computation.
  *      8 = non-temporal loads and stores in pack/unpack (0/1).
  *      9 = as 5, for xs_fused_gather_reduce_sgd (-1 = per dtype).
+ *      10 = fp16 gradients: lanes exchange gradient sums so that parameter/momentum
+ *           accesses of a wavefront are contiguous (0/1).
  * Returns XS_ERR_INVALID_ARG for an unknown key or out-of-range value.
  */
 int xs_tuning_set(int key, int value);

@@ -46,7 +46,7 @@ int compute_units()
 Tuning g_tuning = {/*reduce_wg_per_cu*/ 0, /*copy_wg_per_cu*/ 8, /*nt_loads*/ -1, /*nt_stores*/ -1,
                    /*nt_state_loads*/ -1, /*reduce_lds_reserve*/ -1,
                    /*reduce_max_wg*/ 0, /*copy_max_wg*/ 0, /*copy_nt*/ 1,
-                   /*gather_lds_reserve*/ -1};
+                   /*gather_lds_reserve*/ -1, /*f16_state_shuffle*/ 1};
 
 }  // namespace xs
 
@@ -82,6 +82,7 @@ extern "C" int xs_tuning_set(int key, int value)
     case 7: if (value < 0) break; g_tuning.copy_max_wg = value; return XS_OK;
     case 8: if (value < 0 || value > 1) break; g_tuning.copy_nt = value; return XS_OK;
     case 9: if (value < -1 || value > 65536) break; g_tuning.gather_lds_reserve = value; return XS_OK;
+    case 10: if (value < 0 || value > 1) break; g_tuning.f16_state_shuffle = value; return XS_OK;
     default: return fail(XS_ERR_INVALID_ARG, "xs_tuning_set: unknown key %d", key);
     }
     return fail(XS_ERR_INVALID_ARG, "xs_tuning_set: value %d out of range for key %d", value, key);
@@ -101,6 +102,7 @@ extern "C" int xs_tuning_get(int key, int *value_out)
     case 7: *value_out = g_tuning.copy_max_wg; return XS_OK;
     case 8: *value_out = g_tuning.copy_nt; return XS_OK;
     case 9: *value_out = g_tuning.gather_lds_reserve; return XS_OK;
+    case 10: *value_out = g_tuning.f16_state_shuffle; return XS_OK;
     default: return fail(XS_ERR_INVALID_ARG, "xs_tuning_get: unknown key %d", key);
     }
 }

@@ -108,7 +108,11 @@ struct GatherArgs {
 };
 
 // The vector path for one lane.  `t` is either wave-uniform (scalar address loads) or per lane.
-template <int W, bool F16, bool DETECT, bool VIEWS, bool NTG, bool NTS, bool NTX>
+// SHUF (fp16 gradients, whole wavefront in one tensor, complete row): lanes take state
+// vectors `lane` and `64 + lane` of the row instead of the two under their own gradient
+// vector, and receive the matching gradient sums through the LDS crossbar, so that every
+// state access of the wavefront is one contiguous kilobyte.
+template <int W, bool F16, bool DETECT, bool VIEWS, bool NTG, bool NTS, bool NTX, bool SHUF>
 __device__ __forceinline__ void vector_path(const GatherArgs &a, uint32_t t, uint64_t j, uint64_t k,
                                             bool &bad)
 {
@@ -119,11 +123,25 @@ __device__ __forceinline__ void vector_path(const GatherArgs &a, uint32_t t, uin
 #pragma unroll
     for (int w = 0; w < W; ++w)
         g[w] = load_tensor_vec<NTG, ES>((const gbyte *)a.grad_ptrs[(uint64_t)t * W + w] + k * ES);
+    // state vector q of this lane starts at bucket element sj[q] = tensor element sk[q]
+    uint64_t sj[SV], sk[SV];
+#pragma unroll
+    for (int q = 0; q < SV; ++q) {
+        if constexpr (SHUF) {
+            const uint64_t lane_off = (uint64_t)threadIdx.x * VEC;       // j = row start + lane_off
+            const uint64_t d = (uint64_t)q * 4 * kLanes + 4 * threadIdx.x;
+            sj[q] = j - lane_off + d;
+            sk[q] = k - lane_off + d;
+        } else {
+            sj[q] = j + 4 * q;
+            sk[q] = k + 4 * q;
+        }
+    }
     f32x4 x[SV], v[SV];
 #pragma unroll
     for (int q = 0; q < SV; ++q) {
-        x[q] = load_state<NTX>((const f32x4 *)(a.x_in + j) + q);
-        v[q] = load_state<NTX>((const f32x4 *)(a.v_in + j) + q);
+        x[q] = load_state<NTX>((const f32x4 *)(a.x_in + sj[q]));
+        v[q] = load_state<NTX>((const f32x4 *)(a.v_in + sj[q]));
     }
     float s[VEC];
 #pragma unroll
@@ -144,6 +162,26 @@ __device__ __forceinline__ void vector_path(const GatherArgs &a, uint32_t t, uin
             }
         }
     }
+    if constexpr (SHUF) {
+        // element 4L+e of the row sits in lane L>>1, slot (L&1)*4+e; element 256+4L+e in lane
+        // 32+(L>>1), same slot
+        const int src0 = (int)((threadIdx.x >> 1) << 2);
+        const int src1 = (int)((32u + (threadIdx.x >> 1)) << 2);
+        const bool odd = (threadIdx.x & 1u) != 0u;
+        float t2[VEC];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int lo = __builtin_bit_cast(int, s[e]), hi = __builtin_bit_cast(int, s[4 + e]);
+            const int a_lo = __builtin_amdgcn_ds_bpermute(src0, lo);
+            const int a_hi = __builtin_amdgcn_ds_bpermute(src0, hi);
+            const int b_lo = __builtin_amdgcn_ds_bpermute(src1, lo);
+            const int b_hi = __builtin_amdgcn_ds_bpermute(src1, hi);
+            t2[e] = __builtin_bit_cast(float, odd ? a_hi : a_lo);
+            t2[4 + e] = __builtin_bit_cast(float, odd ? b_hi : b_lo);
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) s[e] = t2[e];
+    }
 #pragma unroll
     for (int q = 0; q < SV; ++q) {
 #pragma unroll
@@ -153,13 +191,13 @@ __device__ __forceinline__ void vector_path(const GatherArgs &a, uint32_t t, uin
             x[q][e] = xe;
             v[q][e] = ve;
         }
-        store_state<NTS>((f32x4 *)(a.x_out + j) + q, x[q]);
-        store_state<NTS>((f32x4 *)(a.v_out + j) + q, v[q]);
+        store_state<NTS>((f32x4 *)(a.x_out + sj[q]), x[q]);
+        store_state<NTS>((f32x4 *)(a.v_out + sj[q]), v[q]);
     }
     if constexpr (VIEWS) {
-        gbyte *dst = (gbyte *)a.param_ptrs[t] + k * 4;
+        gbyte *dst = (gbyte *)a.param_ptrs[t];
 #pragma unroll
-        for (int q = 0; q < SV; ++q) store_tensor_vec<NTS>(dst + 16 * q, x[q]);
+        for (int q = 0; q < SV; ++q) store_tensor_vec<NTS>(dst + sk[q] * 4, x[q]);
     }
 }
 
@@ -186,9 +224,12 @@ __global__ __launch_bounds__(kLanes) void gather_reduce_sgd_kernel(GatherArgs a)
             // every active lane is a full vector of tensor t_row: scalar address loads
             const uint32_t tu = (uint32_t)__builtin_amdgcn_readfirstlane((int)t_row);
             const uint64_t ku = j - a.tb.offsets[tu];
-            vector_path<W, F16, DETECT, VIEWS, NTG, NTS, NTX>(a, tu, j, ku, bad);
+            if (F16 && (row + 1) * ROW <= a.n_bucket)      // complete row: all 64 lanes are here
+                vector_path<W, F16, DETECT, VIEWS, NTG, NTS, NTX, F16>(a, tu, j, ku, bad);
+            else
+                vector_path<W, F16, DETECT, VIEWS, NTG, NTS, NTX, false>(a, tu, j, ku, bad);
         } else if (full) {
-            vector_path<W, F16, DETECT, VIEWS, NTG, NTS, NTX>(a, t, j, k, bad);
+            vector_path<W, F16, DETECT, VIEWS, NTG, NTS, NTX, false>(a, t, j, k, bad);
         } else {
             // element by element: padding contributes +0, elements may belong to later tensors
             uint32_t te = t;
@@ -290,9 +331,8 @@ __global__ __launch_bounds__(kLanes) void gather_reduce_sgd_anyw_kernel(GatherAr
 template <int W, bool F16, bool DETECT, bool VIEWS>
 static void launch_g(const GatherArgs &a, dim3 grid, unsigned lds, hipStream_t stream)
 {
-    // cache hints as in the bucket form: gradients and stores non-temporal; state loads
-    // non-temporal for fp32 only
-    hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, F16, DETECT, VIEWS, true, true, !F16>), grid,
+    // cache hints as in the bucket form: every stream non-temporal
+    hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, F16, DETECT, VIEWS, true, true, true>), grid,
                        dim3(kLanes), lds, stream, a);
 }
 

@@ -36,6 +36,7 @@ struct Tuning {
     int copy_max_wg;          // absolute cap on pack/unpack workgroups (0 = none)
     int copy_nt;              // non-temporal loads and stores in pack/unpack
     int gather_lds_reserve;   // as reduce_lds_reserve, for the gathering form
+    int f16_state_shuffle;    // fp16 gradients: contiguous state vectors per wavefront (see kernel)
 };
 extern Tuning g_tuning;
 

@@ -79,7 +79,7 @@ __device__ __forceinline__ void sgd(float g_sum, float c, float &x, float &v, fl
 
 // VEC elements per lane per trip: 4 (fp32 gradients) or 8 (fp16 gradients), so that
 // every gradient load is 16 bytes wide.
-template <int W, bool F16, bool DETECT, bool NTL, bool NTS, bool NTX>
+template <int W, bool F16, bool DETECT, bool NTL, bool NTS, bool NTX, bool SHUF>
 __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(
     ReplicaPtrs<W> reps, uint64_t n, const float *x_in, const float *v_in,
     float *x_out, float *v_out, float lr, float mu, float wd, float c,
@@ -97,11 +97,27 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(
         u32x4 g[W];
 #pragma unroll
         for (int w = 0; w < W; ++w) g[w] = load_g<NTL>((const u32x4 *)reps.p[w] + i);
+        // Which fp32 state vectors this lane updates.  fp32 gradients: the one under its
+        // gradient vector.  fp16 gradients: a lane's 8 elements would be two neighbouring state
+        // vectors, i.e. 32-byte strides per load instruction; in a full row of 64 lanes the
+        // lanes instead take state vectors `lane` and `64 + lane` of the row, so that every
+        // state load and store of the wavefront is one contiguous kilobyte, and the gradient
+        // sums are moved to the owning lanes through the LDS crossbar afterwards.
+        uint64_t sx[SV];
+        bool shuffled = false;
+        if constexpr (F16) {
+            const uint64_t row0 = i - threadIdx.x;            // vector index of lane 0 (kThreads == 64)
+            shuffled = SHUF && row0 + (kThreads - 1) < nvec;   // uniform: every lane of the row is live
+            sx[0] = shuffled ? row0 * 2 + threadIdx.x : i * 2;
+            sx[1] = shuffled ? row0 * 2 + kThreads + threadIdx.x : i * 2 + 1;
+        } else {
+            sx[0] = i;
+        }
         f32x4 x[SV], v[SV];
 #pragma unroll
         for (int k = 0; k < SV; ++k) {
-            x[k] = load_s<NTX>((const f32x4 *)x_in + i * SV + k);
-            v[k] = load_s<NTX>((const f32x4 *)v_in + i * SV + k);
+            x[k] = load_s<NTX>((const f32x4 *)x_in + sx[k]);
+            v[k] = load_s<NTX>((const f32x4 *)v_in + sx[k]);
         }
         float s[VEC];
 #pragma unroll
@@ -122,6 +138,28 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(
                 }
             }
         }
+        if constexpr (F16) {
+            if (shuffled) {
+                // element 4L+e of the row sits in lane L>>1, slot (L&1)*4+e; element 256+4L+e in
+                // lane 32+(L>>1), same slot
+                const int src0 = (int)((threadIdx.x >> 1) << 2);
+                const int src1 = (int)((32u + (threadIdx.x >> 1)) << 2);
+                const bool odd = (threadIdx.x & 1u) != 0u;
+                float t[VEC];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int lo = __builtin_bit_cast(int, s[e]), hi = __builtin_bit_cast(int, s[4 + e]);
+                    const int a_lo = __builtin_amdgcn_ds_bpermute(src0, lo);
+                    const int a_hi = __builtin_amdgcn_ds_bpermute(src0, hi);
+                    const int b_lo = __builtin_amdgcn_ds_bpermute(src1, lo);
+                    const int b_hi = __builtin_amdgcn_ds_bpermute(src1, hi);
+                    t[e] = __builtin_bit_cast(float, odd ? a_hi : a_lo);
+                    t[4 + e] = __builtin_bit_cast(float, odd ? b_hi : b_lo);
+                }
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) s[e] = t[e];
+            }
+        }
 #pragma unroll
         for (int k = 0; k < SV; ++k) {
 #pragma unroll
@@ -131,8 +169,8 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(
                 x[k][q] = xe;
                 v[k][q] = ve;
             }
-            store_s<NTS>((f32x4 *)x_out + i * SV + k, x[k]);
-            store_s<NTS>((f32x4 *)v_out + i * SV + k, v[k]);
+            store_s<NTS>((f32x4 *)x_out + sx[k], x[k]);
+            store_s<NTS>((f32x4 *)v_out + sx[k], v[k]);
         }
     }
 
@@ -260,6 +298,7 @@ struct LaunchArgs {
     int32_t *found_inf;
     dim3 grid;
     unsigned lds_reserve;
+    bool shuffle;
     hipStream_t stream;
 };
 
@@ -268,9 +307,14 @@ static void launch_one(const LaunchArgs &a)
 {
     ReplicaPtrs<W> r;
     for (int w = 0; w < W; ++w) r.p[w] = a.replicas[w];
-    hipLaunchKernelGGL((reduce_sgd_kernel<W, F16, DETECT, NTL, NTS, NTX>), a.grid, dim3(kThreads),
-                       a.lds_reserve, a.stream, r, a.n, a.x_in, a.v_in, a.x_out, a.v_out, a.lr,
-                       a.mu, a.wd, a.c, a.found_inf);
+    if (F16 && a.shuffle)
+        hipLaunchKernelGGL((reduce_sgd_kernel<W, F16, DETECT, NTL, NTS, NTX, F16>), a.grid,
+                           dim3(kThreads), a.lds_reserve, a.stream, r, a.n, a.x_in, a.v_in, a.x_out,
+                           a.v_out, a.lr, a.mu, a.wd, a.c, a.found_inf);
+    else
+        hipLaunchKernelGGL((reduce_sgd_kernel<W, F16, DETECT, NTL, NTS, NTX, false>), a.grid,
+                           dim3(kThreads), a.lds_reserve, a.stream, r, a.n, a.x_in, a.v_in, a.x_out,
+                           a.v_out, a.lr, a.mu, a.wd, a.c, a.found_inf);
 }
 
 template <int W, bool F16, bool DETECT>
@@ -339,13 +383,15 @@ int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64
     // compute unit; more wavefronts than that only disorder the DRAM access stream.  The
     // LDS reservation (unused by the kernel) caps residency at 10 one-wave workgroups per
     // compute unit for fp32 gradients (12 loads per lane) and 5 for fp16 (20 loads per lane).
-    // fp32: every stream is touched once per lane -> all non-temporal.  fp16: a lane's two
-    // state vectors share cache lines with its neighbours', so state loads stay cacheable.
+    // Every stream is touched once per lane -> all non-temporal (fp16 without the lane
+    // exchange: a lane's two state vectors share cache lines with its neighbours', so state
+    // loads stay cacheable there).
     const int lds_auto = f16 ? 32768 : 16384;
     a.lds_reserve = (unsigned)(g_tuning.reduce_lds_reserve < 0 ? lds_auto : g_tuning.reduce_lds_reserve);
+    a.shuffle = g_tuning.f16_state_shuffle != 0;
     const int ntl = g_tuning.nt_loads < 0 ? 1 : g_tuning.nt_loads;
     const int nts = g_tuning.nt_stores < 0 ? 1 : g_tuning.nt_stores;
-    const int ntx = g_tuning.nt_state_loads < 0 ? (f16 ? 0 : 1) : g_tuning.nt_state_loads;
+    const int ntx = g_tuning.nt_state_loads < 0 ? ((f16 && !a.shuffle) ? 0 : 1) : g_tuning.nt_state_loads;
     const int nt = (ntl ? 1 : 0) | (nts ? 2 : 0) | (ntx ? 4 : 0);
 
     switch (W) {

@@ -39,7 +39,8 @@ TUNE_REDUCE_MAX_WG = 6
 TUNE_COPY_MAX_WG = 7
 TUNE_COPY_NT = 8
 TUNE_GATHER_LDS_RESERVE = 9
-N_TUNING_KEYS = 10
+TUNE_F16_STATE_SHUFFLE = 10
+N_TUNING_KEYS = 11
 
 EXPORTS = [
     "xs_status_string", "xs_last_error", "xs_bucket_layout", "xs_plan_create", "xs_plan_destroy",
