@@ -46,24 +46,19 @@ def _run_gpu(workloads, T, align, fused_gather=False):
             for t, c in zip(tasks, counters)]
     cs, ss = torch.cuda.Stream(), torch.cuda.Stream()
     N = len(apps)
-    outstanding = set()
-    log = []
+    prev = None                      # the task that computed last: its gradients are outstanding
     for t in range(1, T + 1):
         for i in range(N):
-            n = (i + 1) % N
             if N == 1:
                 xs.crossover_step(apps[0], apps[0], cs, ss)
-                log.append(("update", 0, t))
                 continue
-            # Algorithm 1 for two tasks: task i computes while task n's previous gradients
-            # are synchronised; n has nothing outstanding only in the first iteration
-            sync = apps[n] if n in outstanding else None
-            xs.crossover_step(apps[i], sync, cs, ss)
-            outstanding.add(i)
-            if sync is not None:
-                outstanding.discard(n)
-    for n in sorted(outstanding):
-        xs.crossover_drain(apps[n], ss)
+            # Algorithm 1: task i computes while the task that has just sent its gradients is
+            # synchronised; task i's own previous synchronisation is awaited inside the call.
+            # Nothing is outstanding only at the very first inner step.
+            xs.crossover_step(apps[i], apps[prev] if prev is not None else None, cs, ss)
+            prev = i
+    if N > 1 and prev is not None:
+        xs.crossover_drain(apps[prev], ss)
     torch.cuda.synchronize()
     return tasks, apps, counters
 
@@ -101,6 +96,20 @@ def test_two_tasks_match_algorithm_1(T, fused_gather):
             assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
         assert np.array_equal(task.momentum.cpu().numpy().view(np.uint32),
                               state["v"][i].view(np.uint32))
+    for a in apps:
+        a.destroy()
+
+
+def test_three_tasks_match_algorithm_1():
+    wls = [_mini("a", [(300, 7), (64,)], W=2), _mini("b", [(17,), (900, 3)], W=4),
+           _mini("c", [(5000,), (3,), (128,)], W=3)]
+    tasks, apps, counters = _run_gpu(wls, 3, align=4, fused_gather=True)
+    state, log = _run_oracle(wls, 3, 4, tasks)
+    assert [c[0] for c in counters] == [3, 3, 3]
+    assert sum(1 for e in log if e[0] == "bypass") == 2 and sum(1 for e in log if e[0] == "drain") == 2
+    for i, task in enumerate(tasks):
+        for got, want in zip(task.param_tensors, state["p"][i]):
+            assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
     for a in apps:
         a.destroy()
 
