@@ -43,7 +43,7 @@ int compute_units()
 }
 
 // -1 = chosen per gradient dtype at launch (see launch_reduce_sgd)
-Tuning g_tuning = {/*reduce_wg_per_cu*/ 0, /*copy_wg_per_cu*/ 8, /*nt_loads*/ -1, /*nt_stores*/ -1,
+Tuning g_tuning = {/*reduce_wg_per_cu*/ 0, /*copy_wg_per_cu*/ 16, /*nt_loads*/ -1, /*nt_stores*/ -1,
                    /*nt_state_loads*/ -1, /*reduce_lds_reserve*/ -1,
                    /*reduce_max_wg*/ 0, /*copy_max_wg*/ 0, /*copy_nt*/ 1,
                    /*gather_lds_reserve*/ -1, /*f16_state_shuffle*/ 1};
