@@ -26,6 +26,7 @@ _LIB = os.path.join(_HERE, "libxs_oracle.so")
 
 F32 = 0
 F16 = 1
+BF16 = 2      # passed as numpy uint16 arrays holding bfloat16 bit patterns
 
 
 def build(force: bool = False) -> str:
@@ -59,8 +60,9 @@ def lib() -> ctypes.CDLL:
                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float,
                                         ctypes.c_float, ctypes.c_float, ctypes.c_float,
                                         ctypes.c_int]
+        L.xo_round_params.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p]
         for f in (L.xo_layout, L.xo_pack, L.xo_unpack, L.xo_any_nonfinite,
-                  L.xo_reduce_sgd_f64, L.xo_reduce_sgd_f32):
+                  L.xo_reduce_sgd_f64, L.xo_reduce_sgd_f32, L.xo_round_params):
             f.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -88,7 +90,9 @@ def _code(dtype) -> int:
         return F32
     if dt == np.float16:
         return F16
-    raise TypeError(f"gradient dtype {dt} is not float32 or float16")
+    if dt == np.uint16:
+        return BF16
+    raise TypeError(f"gradient dtype {dt} is not float32, float16 or uint16 (bfloat16 bits)")
 
 
 def _check_c(a: np.ndarray, name: str):
@@ -189,6 +193,18 @@ def reduce_sgd_f32(replicas: Sequence[np.ndarray], x: np.ndarray, v: np.ndarray,
                                  float(wd), float(inv_loss_scale), int(threads))
     if rc != 0:
         raise ValueError("W must be >= 1")
+
+
+def round_params(x: np.ndarray, dtype_code: int) -> np.ndarray:
+    """float32 values rounded to binary16 / bfloat16 (ties to even); returns uint16 bit patterns."""
+    _check_c(x, "x")
+    if x.dtype != np.float32:
+        raise TypeError("x must be float32")
+    out = np.empty(x.size, dtype=np.uint16)
+    rc = lib().xo_round_params(x.ctypes.data, x.size, int(dtype_code), out.ctypes.data)
+    if rc != 0:
+        raise ValueError("dtype_code must be F16 or BF16")
+    return out
 
 
 def sync_step(grads: Sequence[Sequence[np.ndarray]], params: Sequence[np.ndarray],

@@ -43,6 +43,7 @@
 
 #define XO_F32 0
 #define XO_F16 1
+#define XO_BF16 2   /* bfloat16: the upper half of an IEEE single */
 
 /* ---- layout: Section 2.1 (tensor fusion) -------------------------------- */
 /* offsets[0] = 0; offsets[t+1] = offsets[t] + numel[t] rounded up to a multiple
@@ -104,9 +105,23 @@ static double half_to_double(uint16_t h)
     return sign ? -v : v;
 }
 
+/* ---- bfloat16 -> double, exact: sign, 8 exponent bits, 7 fraction bits ------- */
+static double bfloat_to_double(uint16_t b)
+{
+    int sign = (b >> 15) & 1;
+    int e = (b >> 7) & 0xff;
+    int m = b & 0x7f;
+    double v;
+    if (e == 0)        v = ldexp((double)m, -133);              /* zero / subnormal: m * 2^-7 * 2^-126 */
+    else if (e == 255) v = (m == 0) ? INFINITY : NAN;
+    else               v = ldexp((double)(128 + m), e - 134);   /* (1 + m/128) * 2^(e-127) */
+    return sign ? -v : v;
+}
+
 static double load_grad(const void *p, int dtype, uint64_t j)
 {
     if (dtype == XO_F16) return half_to_double(((const uint16_t *)p)[j]);
+    if (dtype == XO_BF16) return bfloat_to_double(((const uint16_t *)p)[j]);
     return (double)((const float *)p)[j];
 }
 
@@ -177,5 +192,43 @@ int xo_reduce_sgd_f32(const void *const *replicas, uint32_t W, int dtype, uint64
         v[j] = vn;
         x[j] = x[j] - lv;
     }
+    return 0;
+}
+
+/* ---- half-precision copy of the updated parameters (mixed-precision workload) -------- */
+/* Round each single-precision value to the nearest binary16 / bfloat16, ties to even,
+ * written out on the value (frexp/ldexp/nearbyint), not on the bit pattern.  Overflow goes
+ * to infinity, NaN stays NaN (quiet, sign kept), results below the smallest normal are
+ * rounded on the subnormal grid. */
+static uint16_t round_to_small_float(float xf, int exp_bits, int frac_bits)
+{
+    const int bias = (1 << (exp_bits - 1)) - 1;
+    const int emax = bias;                 /* largest finite exponent */
+    const int emin = 1 - bias;             /* smallest normal exponent */
+    uint16_t sign = signbit(xf) ? (uint16_t)(1u << (exp_bits + frac_bits)) : 0;
+    const uint16_t exp_all = (uint16_t)(((1u << exp_bits) - 1) << frac_bits);
+    if (isnan(xf)) return (uint16_t)(sign | exp_all | (1u << (frac_bits - 1)));
+    if (isinf(xf)) return (uint16_t)(sign | exp_all);
+    double a = fabs((double)xf);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                    /* a = f * 2^e, f in [0.5, 1)  =>  a in [2^(e-1), 2^e) */
+    int ex = e - 1;                        /* a = m * 2^ex, m in [1, 2) */
+    if (ex < emin) ex = emin;              /* subnormal grid shares the smallest normal's spacing */
+    double q = ldexp(a, frac_bits - ex);   /* in units of the last place */
+    double r = nearbyint(q);               /* ties to even in the default rounding mode */
+    if (r >= ldexp(1.0, frac_bits + 1)) { r = ldexp(r, -1); ex += 1; }   /* rounded up to 2.0 */
+    if (ex > emax) return (uint16_t)(sign | exp_all);                     /* overflow */
+    uint32_t ri = (uint32_t)r;
+    if (ri < (1u << frac_bits)) return (uint16_t)(sign | ri);             /* subnormal or zero */
+    return (uint16_t)(sign | (uint32_t)((ex + bias) << frac_bits) | (ri - (1u << frac_bits)));
+}
+
+int xo_round_params(const float *x, uint64_t n, int dtype, uint16_t *out)
+{
+    if (dtype != XO_F16 && dtype != XO_BF16) return -1;
+    for (uint64_t j = 0; j < n; ++j)
+        out[j] = (dtype == XO_F16) ? round_to_small_float(x[j], 5, 10)
+                                   : round_to_small_float(x[j], 8, 7);
     return 0;
 }

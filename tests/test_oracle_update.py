@@ -271,3 +271,48 @@ def test_finite_half_sum_cannot_overflow_single():
     x = np.zeros(2, np.float32); v = np.zeros(2, np.float32)
     oracle.reduce_sgd_f32(reps, x, v, 1.0, 0.0, 0.0, 1.0)
     assert np.all(v == 65504.0)
+
+
+# ------------------------------------------------------------------ bfloat16 gradients, half copies
+def _bf16_bits(t: torch.Tensor) -> np.ndarray:
+    return t.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def test_bfloat16_gradients_equal_their_widened_values():
+    rng = np.random.default_rng(14)
+    n, W = 500, 4
+    vals = [torch.tensor(rng.standard_normal(n), dtype=torch.float32) for _ in range(W)]
+    vals[0][:6] = torch.tensor([1e-40, -1e-40, 3.3895e38, -3.3895e38, 0.0, -0.0])   # subnormal, max
+    bits = [_bf16_bits(v) for v in vals]
+    widened = [v.to(torch.bfloat16).to(torch.float32).numpy() for v in vals]         # library widening
+    for fn, dt in ((oracle.reduce_sgd_f64, np.float64), (oracle.reduce_sgd_f32, np.float32)):
+        xa = np.ones(n, dt); va = np.zeros(n, dt); xb = xa.copy(); vb = va.copy()
+        fn(bits, xa, va, 0.1, 0.9, 1e-4, 1.0 / 128)
+        fn(widened, xb, vb, 0.1, 0.9, 1e-4, 1.0 / 128)
+        assert np.array_equal(xa, xb) and np.array_equal(va, vb)
+    inf_bits = bits[1].copy(); inf_bits[7] = 0x7f80
+    assert oracle.any_nonfinite([bits[0], inf_bits], [n], oracle.layout([n]))
+    nan_bits = bits[1].copy(); nan_bits[7] = 0xffc1
+    assert oracle.any_nonfinite([nan_bits], [n], oracle.layout([n]))
+    assert not oracle.any_nonfinite(bits, [n], oracle.layout([n]))
+
+
+def test_round_params_matches_library_conversions():
+    rng = np.random.default_rng(15)
+    x = np.concatenate([
+        rng.standard_normal(20000).astype(np.float32),
+        (rng.standard_normal(5000) * 1e-6).astype(np.float32),         # fp16 subnormal range
+        (rng.standard_normal(5000) * 1e5).astype(np.float32),          # fp16 overflow range
+        np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 65504.0, 65519.9, 65520.0, -65520.0,
+                  2.0 ** -24, 2.0 ** -25, 1.5 * 2.0 ** -25, 2.0 ** -14, 1.0009765625, 1.00048828125,
+                  1.00146484375, 3.3895314e38, 3.4e38, 1e-40, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -9],
+                 dtype=np.float32)])
+    h = oracle.round_params(x, oracle.F16)
+    want_h = x.astype(np.float16).view(np.uint16)
+    nan = np.isnan(x)
+    assert np.array_equal(h[~nan], want_h[~nan])
+    assert np.all((h[nan] & 0x7c00) == 0x7c00) and np.all((h[nan] & 0x03ff) != 0)
+    b = oracle.round_params(x, oracle.BF16)
+    want_b = _bf16_bits(torch.from_numpy(x.copy()))
+    assert np.array_equal(b[~nan], want_b[~nan])
+    assert np.all((b[nan] & 0x7f80) == 0x7f80) and np.all((b[nan] & 0x007f) != 0)
