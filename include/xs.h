@@ -55,7 +55,7 @@ typedef enum {
     XS_ERR_STATE       = -7   /* crossover call out of order (nothing to synchronise) */
 } xs_status;
 
-typedef enum { XS_F32 = 0, XS_F16 = 1 } xs_dtype;   /* gradient element type */
+typedef enum { XS_F32 = 0, XS_F16 = 1, XS_BF16 = 2 } xs_dtype;   /* element types */
 
 /* Static string for a status code. */
 const char *xs_status_string(int status);
@@ -145,6 +145,28 @@ int xs_fused_reduce_sgd(const void *const *replica_buckets, uint32_t W, int grad
                         float *params_out, float *momentum_out,
                         const xs_sgd_hparams *hp, int32_t *found_inf, void *hip_stream);
 
+/* Mixed-precision outputs (beyond the paper: the practical surface around SGD(x, g) when the
+ * model computes in half precision and the optimizer keeps fp32 master weights).
+ *   model_copy        xs_fused_reduce_sgd_mp only: device, 16-byte aligned, n_elems half-
+ *                     precision elements in bucket layout, or NULL.  Receives the updated
+ *                     parameters rounded to nearest even, in the same pass (+2 bytes/element).
+ *   model_copy_dtype  XS_F16 or XS_BF16.
+ *   view_dtype        xs_fused_gather_reduce_sgd_mp only: element type of the per-layer views
+ *                     that param_tensor_ptrs point to: XS_F32, XS_F16 or XS_BF16.
+ * A NULL xs_mp_options pointer means: no model copy, fp32 views.
+ */
+typedef struct {
+    void *model_copy;
+    int model_copy_dtype;
+    int view_dtype;
+} xs_mp_options;
+
+int xs_fused_reduce_sgd_mp(const void *const *replica_buckets, uint32_t W, int grad_dtype,
+                           uint64_t n_elems, float *params, float *momentum,
+                           float *params_out, float *momentum_out,
+                           const xs_sgd_hparams *hp, int32_t *found_inf,
+                           const xs_mp_options *mp, void *hip_stream);
+
 /* ------------------------------------------------------------------------
  * The same pass without materialised buckets (Section 2.1 fuses the tensors only
  * because the fused tensor has to be sent; on one GPU the layout alone suffices):
@@ -169,6 +191,13 @@ int xs_fused_gather_reduce_sgd(const xs_plan *gradient_plan, const void *const *
                                float *params_out, float *momentum_out,
                                void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
                                int32_t *found_inf, void *hip_stream);
+/* As above with mixed-precision options: mp->view_dtype selects half-precision views;
+ * mp->model_copy must be NULL here (XS_ERR_UNSUPPORTED otherwise). */
+int xs_fused_gather_reduce_sgd_mp(const xs_plan *gradient_plan, const void *const *grad_ptrs,
+                                  uint32_t W, float *params, float *momentum,
+                                  float *params_out, float *momentum_out,
+                                  void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
+                                  int32_t *found_inf, const xs_mp_options *mp, void *hip_stream);
 
 /* ------------------------------------------------------------------------
  * Training task ("distributed task i" of Algorithm 1) as seen by the scheduler.
@@ -237,24 +266,24 @@ int xs_app_wait_sync(xs_app *app, void *hip_stream);
 int xs_standin_alu(uint32_t workgroups, uint32_t iters, float *sink, void *hip_stream);
 
 /* ------------------------------------------------------------------------
- * Launch tuning (process-wide; defaults are the measured best for MI355X).
- * key: 0 = reduce kernel workgroups per compute unit for a grid-stride launch
- *          (0 = one 16-byte vector per lane, no loop),
- *      1 = pack/unpack workgroups per compute unit,
- *      2 = non-temporal loads of gradient replicas (0/1),
- *      3 = non-temporal stores of parameters and momentum (0/1),
- *      4 = non-temporal loads of parameters and momentum (0/1),
- *      5 = bytes of LDS reserved per reduce workgroup; the kernel does not use LDS,
- *          the reservation only caps how many wavefronts share a compute unit.
- *      Keys 2-5 also accept -1 (the default): chosen per gradient dtype.
- *      6 = absolute cap on reduce workgroups, 7 = on pack/unpack workgroups (0 = none):
- *          paces a synchronisation that runs beside another task's computation.
- *      8 = non-temporal loads and stores in pack/unpack (0/1).
- *      9 = as 5, for xs_fused_gather_reduce_sgd (-1 = per dtype).
- *      10 = fp16 gradients: lanes exchange gradient sums so that parameter/momentum
- *           accesses of a wavefront are contiguous (0/1).
- * Returns XS_ERR_INVALID_ARG for an unknown key or out-of-range value.
+ * Launch tuning (process-wide; the defaults are the measured best for MI355X).
+ * Returns XS_ERR_INVALID_ARG for an unknown key or an out-of-range value.
  */
+typedef enum {
+    XS_TUNE_REDUCE_WG_PER_CU = 0,   /* reduce kernels: workgroups per compute unit for a grid-stride
+                                       launch; 0 (default) = one 16-byte vector per lane, no loop */
+    XS_TUNE_COPY_WG_PER_CU = 1,     /* pack/unpack: workgroups per compute unit (default 16) */
+    XS_TUNE_NT_GRADS = 2,           /* bucket-form reduce: non-temporal gradient loads (0/1, default 1) */
+    XS_TUNE_NT_STATE = 3,           /* bucket-form reduce: non-temporal parameter/momentum accesses (0/1, default 1) */
+    XS_TUNE_REDUCE_LDS_RESERVE = 4, /* bytes of LDS reserved per reduce workgroup; the kernel uses no
+                                       LDS, the reservation caps how many wavefronts share a compute
+                                       unit; -1 (default) = 16384 for fp32, 32768 for half precision */
+    XS_TUNE_REDUCE_MAX_WG = 5,      /* absolute cap on reduce workgroups, 0 = none: paces a */
+    XS_TUNE_COPY_MAX_WG = 6,        /*   synchronisation that runs beside another task's computation */
+    XS_TUNE_COPY_NT = 7,            /* pack/unpack: non-temporal accesses (0/1, default 1) */
+    XS_TUNE_GATHER_LDS_RESERVE = 8, /* as 4 for the gathering form; -1 = 8192 fp32, 16384 half */
+    XS_TUNE_COUNT = 9
+} xs_tuning_key;
 int xs_tuning_set(int key, int value);
 int xs_tuning_get(int key, int *value_out);
 

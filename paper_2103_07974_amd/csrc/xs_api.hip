@@ -43,10 +43,9 @@ int compute_units()
 }
 
 // -1 = chosen per gradient dtype at launch (see launch_reduce_sgd)
-Tuning g_tuning = {/*reduce_wg_per_cu*/ 0, /*copy_wg_per_cu*/ 16, /*nt_loads*/ -1, /*nt_stores*/ -1,
-                   /*nt_state_loads*/ -1, /*reduce_lds_reserve*/ -1,
-                   /*reduce_max_wg*/ 0, /*copy_max_wg*/ 0, /*copy_nt*/ 1,
-                   /*gather_lds_reserve*/ -1, /*f16_state_shuffle*/ 1};
+Tuning g_tuning = {/*reduce_wg_per_cu*/ 0, /*copy_wg_per_cu*/ 16, /*nt_grads*/ 1, /*nt_state*/ 1,
+                   /*reduce_lds_reserve*/ -1, /*reduce_max_wg*/ 0, /*copy_max_wg*/ 0,
+                   /*copy_nt*/ 1, /*gather_lds_reserve*/ -1};
 
 }  // namespace xs
 
@@ -69,42 +68,42 @@ extern "C" const char *xs_status_string(int status)
 
 extern "C" const char *xs_last_error(void) { return t_error; }
 
+namespace {
+struct TuningSlot {
+    int xs::Tuning::*field;
+    int lo, hi;
+};
+const TuningSlot kTuning[XS_TUNE_COUNT] = {
+    {&xs::Tuning::reduce_wg_per_cu, 0, 64},       // XS_TUNE_REDUCE_WG_PER_CU
+    {&xs::Tuning::copy_wg_per_cu, 1, 64},         // XS_TUNE_COPY_WG_PER_CU
+    {&xs::Tuning::nt_grads, 0, 1},                // XS_TUNE_NT_GRADS
+    {&xs::Tuning::nt_state, 0, 1},                // XS_TUNE_NT_STATE
+    {&xs::Tuning::reduce_lds_reserve, -1, 65536}, // XS_TUNE_REDUCE_LDS_RESERVE
+    {&xs::Tuning::reduce_max_wg, 0, 0x7fffffff},  // XS_TUNE_REDUCE_MAX_WG
+    {&xs::Tuning::copy_max_wg, 0, 0x7fffffff},    // XS_TUNE_COPY_MAX_WG
+    {&xs::Tuning::copy_nt, 0, 1},                 // XS_TUNE_COPY_NT
+    {&xs::Tuning::gather_lds_reserve, -1, 65536}, // XS_TUNE_GATHER_LDS_RESERVE
+};
+}  // namespace
+
 extern "C" int xs_tuning_set(int key, int value)
 {
-    switch (key) {
-    case 0: if (value < 0 || value > 64) break; g_tuning.reduce_wg_per_cu = value; return XS_OK;
-    case 1: if (value < 1 || value > 64) break; g_tuning.copy_wg_per_cu = value; return XS_OK;
-    case 2: if (value < -1 || value > 1) break; g_tuning.nt_loads = value; return XS_OK;
-    case 3: if (value < -1 || value > 1) break; g_tuning.nt_stores = value; return XS_OK;
-    case 4: if (value < -1 || value > 1) break; g_tuning.nt_state_loads = value; return XS_OK;
-    case 5: if (value < -1 || value > 65536) break; g_tuning.reduce_lds_reserve = value; return XS_OK;
-    case 6: if (value < 0) break; g_tuning.reduce_max_wg = value; return XS_OK;
-    case 7: if (value < 0) break; g_tuning.copy_max_wg = value; return XS_OK;
-    case 8: if (value < 0 || value > 1) break; g_tuning.copy_nt = value; return XS_OK;
-    case 9: if (value < -1 || value > 65536) break; g_tuning.gather_lds_reserve = value; return XS_OK;
-    case 10: if (value < 0 || value > 1) break; g_tuning.f16_state_shuffle = value; return XS_OK;
-    default: return fail(XS_ERR_INVALID_ARG, "xs_tuning_set: unknown key %d", key);
-    }
-    return fail(XS_ERR_INVALID_ARG, "xs_tuning_set: value %d out of range for key %d", value, key);
+    if (key < 0 || key >= XS_TUNE_COUNT)
+        return fail(XS_ERR_INVALID_ARG, "xs_tuning_set: unknown key %d", key);
+    if (value < kTuning[key].lo || value > kTuning[key].hi)
+        return fail(XS_ERR_INVALID_ARG, "xs_tuning_set: value %d out of range [%d, %d] for key %d",
+                    value, kTuning[key].lo, kTuning[key].hi, key);
+    g_tuning.*(kTuning[key].field) = value;
+    return XS_OK;
 }
 
 extern "C" int xs_tuning_get(int key, int *value_out)
 {
     if (!value_out) return fail(XS_ERR_INVALID_ARG, "xs_tuning_get: value_out is NULL");
-    switch (key) {
-    case 0: *value_out = g_tuning.reduce_wg_per_cu; return XS_OK;
-    case 1: *value_out = g_tuning.copy_wg_per_cu; return XS_OK;
-    case 2: *value_out = g_tuning.nt_loads; return XS_OK;
-    case 3: *value_out = g_tuning.nt_stores; return XS_OK;
-    case 4: *value_out = g_tuning.nt_state_loads; return XS_OK;
-    case 5: *value_out = g_tuning.reduce_lds_reserve; return XS_OK;
-    case 6: *value_out = g_tuning.reduce_max_wg; return XS_OK;
-    case 7: *value_out = g_tuning.copy_max_wg; return XS_OK;
-    case 8: *value_out = g_tuning.copy_nt; return XS_OK;
-    case 9: *value_out = g_tuning.gather_lds_reserve; return XS_OK;
-    case 10: *value_out = g_tuning.f16_state_shuffle; return XS_OK;
-    default: return fail(XS_ERR_INVALID_ARG, "xs_tuning_get: unknown key %d", key);
-    }
+    if (key < 0 || key >= XS_TUNE_COUNT)
+        return fail(XS_ERR_INVALID_ARG, "xs_tuning_get: unknown key %d", key);
+    *value_out = g_tuning.*(kTuning[key].field);
+    return XS_OK;
 }
 
 // Section 2.1, tensor fusion: tensors laid end to end, each start rounded up.
@@ -131,6 +130,7 @@ static int elem_size_of(int dtype)
     switch (dtype) {
     case XS_F32: return 4;
     case XS_F16: return 2;
+    case XS_BF16: return 2;
     default: return 0;
     }
 }
@@ -275,11 +275,21 @@ static bool overlaps(const void *a, uint64_t a_bytes, const void *b, uint64_t b_
     return a0 < b0 + b_bytes && b0 < a0 + a_bytes;
 }
 
-extern "C" int xs_fused_reduce_sgd(const void *const *replica_buckets, uint32_t W, int grad_dtype,
-                                   uint64_t n_elems, float *params, float *momentum,
-                                   float *params_out, float *momentum_out,
-                                   const xs_sgd_hparams *hp, int32_t *found_inf, void *hip_stream)
+static bool is_half_dtype(int dtype) { return dtype == XS_F16 || dtype == XS_BF16; }
+
+extern "C" int xs_fused_reduce_sgd_mp(const void *const *replica_buckets, uint32_t W, int grad_dtype,
+                                      uint64_t n_elems, float *params, float *momentum,
+                                      float *params_out, float *momentum_out,
+                                      const xs_sgd_hparams *hp, int32_t *found_inf,
+                                      const xs_mp_options *mp, void *hip_stream)
 {
+    void *model_copy = mp ? mp->model_copy : nullptr;
+    const int model_copy_dtype = mp ? mp->model_copy_dtype : XS_F16;
+    if (model_copy && !is_half_dtype(model_copy_dtype))
+        return fail(XS_ERR_UNSUPPORTED, "xs_fused_reduce_sgd: model_copy_dtype %d is not XS_F16 or XS_BF16",
+                    model_copy_dtype);
+    if (model_copy && !aligned16(model_copy))
+        return fail(XS_ERR_ALIGNMENT, "xs_fused_reduce_sgd: model_copy is not 16-byte aligned");
     const int es = elem_size_of(grad_dtype);
     if (es == 0) return fail(XS_ERR_UNSUPPORTED, "xs_fused_reduce_sgd: unknown grad_dtype %d", grad_dtype);
     if (W == 0 || W > XS_MAX_REPLICAS)
@@ -315,20 +325,45 @@ extern "C" int xs_fused_reduce_sgd(const void *const *replica_buckets, uint32_t 
                 return fail(XS_ERR_INVALID_ARG,
                             "xs_fused_reduce_sgd: replica_buckets[%u] overlaps a parameter/momentum buffer", w);
     }
+    if (model_copy) {
+        for (int a = 0; a < n_state; ++a)
+            if (overlaps(model_copy, n_elems * 2, state[a], sbytes))
+                return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd: model_copy overlaps a parameter/momentum buffer");
+        for (uint32_t w = 0; w < W; ++w)
+            if (overlaps(model_copy, n_elems * 2, replica_buckets[w], gbytes))
+                return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd: model_copy overlaps replica_buckets[%u]", w);
+    }
     return launch_reduce_sgd(replica_buckets, W, grad_dtype, n_elems, params, momentum,
                              out_of_place ? params_out : params,
                              out_of_place ? momentum_out : momentum, *hp, found_inf,
-                             /*detect=*/out_of_place && found_inf != nullptr,
-                             (hipStream_t)hip_stream);
+                             /*detect=*/out_of_place && found_inf != nullptr, model_copy,
+                             model_copy_dtype, (hipStream_t)hip_stream);
+}
+
+extern "C" int xs_fused_reduce_sgd(const void *const *replica_buckets, uint32_t W, int grad_dtype,
+                                   uint64_t n_elems, float *params, float *momentum,
+                                   float *params_out, float *momentum_out,
+                                   const xs_sgd_hparams *hp, int32_t *found_inf, void *hip_stream)
+{
+    return xs_fused_reduce_sgd_mp(replica_buckets, W, grad_dtype, n_elems, params, momentum,
+                                  params_out, momentum_out, hp, found_inf, nullptr, hip_stream);
 }
 
 // ---- the same pass reading the per-layer gradient tensors directly ----------------------
-extern "C" int xs_fused_gather_reduce_sgd(const xs_plan *gradient_plan, const void *const *grad_ptrs,
-                                          uint32_t W, float *params, float *momentum,
-                                          float *params_out, float *momentum_out,
-                                          void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
-                                          int32_t *found_inf, void *hip_stream)
+extern "C" int xs_fused_gather_reduce_sgd_mp(const xs_plan *gradient_plan, const void *const *grad_ptrs,
+                                             uint32_t W, float *params, float *momentum,
+                                             float *params_out, float *momentum_out,
+                                             void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
+                                             int32_t *found_inf, const xs_mp_options *mp,
+                                             void *hip_stream)
 {
+    const int view_dtype = mp ? mp->view_dtype : XS_F32;
+    if (view_dtype != XS_F32 && !is_half_dtype(view_dtype))
+        return fail(XS_ERR_UNSUPPORTED, "xs_fused_gather_reduce_sgd: unknown view_dtype %d", view_dtype);
+    if (mp && mp->model_copy)
+        return fail(XS_ERR_UNSUPPORTED,
+                    "xs_fused_gather_reduce_sgd: model_copy is not available in the gathering form; "
+                    "use half-precision parameter views (view_dtype)");
     if (!gradient_plan || gradient_plan->magic != XS_PLAN_MAGIC)
         return fail(XS_ERR_INVALID_ARG, "xs_fused_gather_reduce_sgd: plan is NULL or not a plan");
     if (W == 0 || W > XS_MAX_REPLICAS)
@@ -362,6 +397,17 @@ extern "C" int xs_fused_gather_reduce_sgd(const xs_plan *gradient_plan, const vo
                 return fail(XS_ERR_INVALID_ARG, "xs_fused_gather_reduce_sgd: params/momentum buffers overlap");
     return launch_gather_reduce_sgd(gradient_plan, grad_ptrs, W, params, momentum,
                                     out_of_place ? params_out : params,
-                                    out_of_place ? momentum_out : momentum, param_tensor_ptrs, *hp,
-                                    found_inf, detect, (hipStream_t)hip_stream);
+                                    out_of_place ? momentum_out : momentum, param_tensor_ptrs,
+                                    view_dtype, *hp, found_inf, detect, (hipStream_t)hip_stream);
+}
+
+extern "C" int xs_fused_gather_reduce_sgd(const xs_plan *gradient_plan, const void *const *grad_ptrs,
+                                          uint32_t W, float *params, float *momentum,
+                                          float *params_out, float *momentum_out,
+                                          void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
+                                          int32_t *found_inf, void *hip_stream)
+{
+    return xs_fused_gather_reduce_sgd_mp(gradient_plan, grad_ptrs, W, params, momentum, params_out,
+                                         momentum_out, param_tensor_ptrs, hp, found_inf, nullptr,
+                                         hip_stream);
 }

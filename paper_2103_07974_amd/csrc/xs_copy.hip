@@ -16,21 +16,18 @@
 //
 // HBM-bound: 2*s bytes per element (read once, written once); no arithmetic
 // except the exponent test that raises the overflow flag while packing.
+#include "xs_device.h"
 #include "xs_internal.h"
 
 namespace xs {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-// tensor addresses arrive as integers; say that they are global memory so that the
-// copies compile to global_* rather than flat_* instructions
-typedef __attribute__((address_space(1))) unsigned char gbyte;
+// Tensor addresses arrive as integers; the global address space on them (gbyte, gvec) makes
+// the copies compile to global_* rather than flat_* instructions.
 
 template <int ALIGN>
 struct __attribute__((packed, aligned(ALIGN))) LooseVec {
     u32x4 v;
 };
-
-typedef __attribute__((address_space(1))) u32x4 gvec;
 
 // 16-byte accesses with or without the non-temporal hint.  The element-aligned ("loose")
 // forms go through a packed struct so that the compiler may assume only ES-byte alignment;
@@ -81,20 +78,6 @@ __device__ __forceinline__ uint32_t find_tensor(Table table, uint32_t count, uin
 }
 
 template <int ES>
-__device__ __forceinline__ bool nonfinite_word(uint32_t w)
-{
-    if constexpr (ES == 4) return (w & 0x7f800000u) == 0x7f800000u;
-    else return (((w & 0x7c007c00u) + 0x04000400u) & 0x80008000u) != 0u;
-}
-
-template <int ES>
-__device__ __forceinline__ bool nonfinite_elem(uint32_t bits)
-{
-    if constexpr (ES == 4) return (bits & 0x7f800000u) == 0x7f800000u;
-    else return (bits & 0x7c00u) == 0x7c00u;
-}
-
-template <int ES>
 struct Elem;
 template <>
 struct Elem<4> { typedef uint32_t type; };
@@ -103,11 +86,13 @@ struct Elem<2> { typedef uint16_t type; };
 
 // UNPACK = false: tensors -> bucket (padding zero-filled, optional overflow flag)
 // UNPACK = true : bucket -> tensors (padding skipped)
-template <bool UNPACK, bool DETECT, int ES, bool LDS_TABLE, bool NT>
+// DT: element type of the plan (XS_F32 / XS_F16 / XS_BF16); it matters only for the overflow test.
+template <bool UNPACK, bool DETECT, int DT, bool LDS_TABLE, bool NT>
 __global__ __launch_bounds__(kCopyThreads) void copy_kernel(
     PlanTables tb, uint32_t n_tensors, uint32_t n_chunks, const uintptr_t *tensor_ptrs,
     unsigned char *bucket, int32_t *found_inf)
 {
+    constexpr int ES = Grad<DT>::ES;
     typedef typename Elem<ES>::type elem_t;
     typedef __attribute__((address_space(1))) elem_t gelem;
     extern __shared__ uint32_t s_prefix[];
@@ -162,8 +147,8 @@ __global__ __launch_bounds__(kCopyThreads) void copy_kernel(
                 else {
                     store_vec<NT>((gvec *)(b + lo), r[u]);
                     if constexpr (DETECT)
-                        bad = bad || nonfinite_word<ES>(r[u][0]) || nonfinite_word<ES>(r[u][1]) ||
-                              nonfinite_word<ES>(r[u][2]) || nonfinite_word<ES>(r[u][3]);
+                        bad = bad || Grad<DT>::nonfinite(r[u][0]) || Grad<DT>::nonfinite(r[u][1]) ||
+                              Grad<DT>::nonfinite(r[u][2]) || Grad<DT>::nonfinite(r[u][3]);
                 }
             } else if (j < nvec) {
                 const int32_t e0 = lo < 0 ? 0 : lo;
@@ -174,7 +159,7 @@ __global__ __launch_bounds__(kCopyThreads) void copy_kernel(
                         else {
                             const elem_t bits = *(const gelem *)(q + e);
                             *(gelem *)(b + e) = bits;
-                            if constexpr (DETECT) bad |= nonfinite_elem<ES>(bits);
+                            if constexpr (DETECT) bad |= Grad<DT>::nonfinite_elem(bits);
                         }
                     } else if constexpr (!UNPACK) {
                         *(gelem *)(b + e) = (elem_t)0;
@@ -190,7 +175,7 @@ __global__ __launch_bounds__(kCopyThreads) void copy_kernel(
     }
 }
 
-template <bool UNPACK, bool DETECT, int ES>
+template <bool UNPACK, bool DETECT, int DT>
 static int launch_copy(const xs_plan *plan, const void *tensor_ptrs, void *bucket,
                        int32_t *found_inf, hipStream_t stream)
 {
@@ -205,7 +190,7 @@ static int launch_copy(const xs_plan *plan, const void *tensor_ptrs, void *bucke
     const bool nt = g_tuning.copy_nt != 0;
     const dim3 grid(blocks), block(kCopyThreads);
 #define XS_COPY_LAUNCH(LDS, NT)                                                                   \
-    hipLaunchKernelGGL((copy_kernel<UNPACK, DETECT, ES, LDS, NT>), grid, block, (LDS) ? lds_bytes : 0, \
+    hipLaunchKernelGGL((copy_kernel<UNPACK, DETECT, DT, LDS, NT>), grid, block, (LDS) ? lds_bytes : 0, \
                        stream, plan->tables, plan->n_tensors, plan->n_chunks,                     \
                        (const uintptr_t *)tensor_ptrs, (unsigned char *)bucket, found_inf)
     if (lds) { if (nt) XS_COPY_LAUNCH(true, true); else XS_COPY_LAUNCH(true, false); }
@@ -218,19 +203,23 @@ static int launch_copy(const xs_plan *plan, const void *tensor_ptrs, void *bucke
 int launch_pack(const xs_plan *plan, const void *const *tensor_ptrs, void *bucket,
                 int32_t *found_inf, hipStream_t stream)
 {
-    if (plan->elem_size == 4)
-        return found_inf ? launch_copy<false, true, 4>(plan, tensor_ptrs, bucket, found_inf, stream)
-                         : launch_copy<false, false, 4>(plan, tensor_ptrs, bucket, nullptr, stream);
-    return found_inf ? launch_copy<false, true, 2>(plan, tensor_ptrs, bucket, found_inf, stream)
-                     : launch_copy<false, false, 2>(plan, tensor_ptrs, bucket, nullptr, stream);
+    if (!found_inf)   // a plain copy: only the element size matters
+        return plan->elem_size == 4
+                   ? launch_copy<false, false, XS_F32>(plan, tensor_ptrs, bucket, nullptr, stream)
+                   : launch_copy<false, false, XS_F16>(plan, tensor_ptrs, bucket, nullptr, stream);
+    switch (plan->dtype) {
+    case XS_F16: return launch_copy<false, true, XS_F16>(plan, tensor_ptrs, bucket, found_inf, stream);
+    case XS_BF16: return launch_copy<false, true, XS_BF16>(plan, tensor_ptrs, bucket, found_inf, stream);
+    default: return launch_copy<false, true, XS_F32>(plan, tensor_ptrs, bucket, found_inf, stream);
+    }
 }
 
 int launch_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,
                   hipStream_t stream)
 {
     if (plan->elem_size == 4)
-        return launch_copy<true, false, 4>(plan, tensor_ptrs, const_cast<void *>(bucket), nullptr, stream);
-    return launch_copy<true, false, 2>(plan, tensor_ptrs, const_cast<void *>(bucket), nullptr, stream);
+        return launch_copy<true, false, XS_F32>(plan, tensor_ptrs, const_cast<void *>(bucket), nullptr, stream);
+    return launch_copy<true, false, XS_F16>(plan, tensor_ptrs, const_cast<void *>(bucket), nullptr, stream);
 }
 
 }  // namespace xs

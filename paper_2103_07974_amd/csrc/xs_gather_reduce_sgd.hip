@@ -18,79 +18,43 @@
 // path (element-aligned 16-byte loads from the tensors); vectors that touch padding or
 // straddle tensors (tight layouts) go element by element, with padding contributing +0
 // exactly as a packed bucket would.
+#include "xs_device.h"
 #include "xs_internal.h"
 
 namespace xs {
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(1))) unsigned char gbyte;
-typedef __attribute__((address_space(1))) u32x4 gvec;
-
 template <int ALIGN>
-struct __attribute__((packed, aligned(ALIGN))) LooseVec {
+struct __attribute__((packed, aligned(ALIGN))) LooseVec16 {
     u32x4 v;
 };
+struct __attribute__((packed, aligned(2))) LooseVec8 {
+    u32x2 v;
+};
 
-constexpr int kLanes = 64;
-
-template <bool NT, int ES>
+// element-aligned 16-byte load from a gradient tensor (non-temporal when it happens to be aligned)
+template <int ES>
 __device__ __forceinline__ u32x4 load_tensor_vec(const gbyte *p)
 {
-    if constexpr (NT) {
-        if (((uintptr_t)p & 15u) == 0) return __builtin_nontemporal_load((const gvec *)p);
+    if (((uintptr_t)p & 15u) == 0) return __builtin_nontemporal_load((const gvec *)p);
+    return ((const __attribute__((address_space(1))) LooseVec16<ES> *)p)->v;
+}
+
+// four updated parameters to a per-layer view: fp32 (16 bytes) or half precision (8 bytes)
+__device__ __forceinline__ void store_view4(gbyte *view, uint64_t elem, f32x4 x, int view_dtype)
+{
+    if (view_dtype == XS_F32) {
+        gbyte *p = view + elem * 4;
+        const u32x4 bits = __builtin_bit_cast(u32x4, x);
+        if (((uintptr_t)p & 15u) == 0) __builtin_nontemporal_store(bits, (gvec *)p);
+        else ((__attribute__((address_space(1))) LooseVec16<4> *)p)->v = bits;
+    } else {
+        ((__attribute__((address_space(1))) LooseVec8 *)(view + elem * 2))->v = to_half4(x, view_dtype);
     }
-    return ((const __attribute__((address_space(1))) LooseVec<ES> *)p)->v;
 }
-
-template <bool NT>
-__device__ __forceinline__ void store_tensor_vec(gbyte *p, f32x4 v)
+__device__ __forceinline__ void store_view1(gbyte *view, uint64_t elem, float x, int view_dtype)
 {
-    const u32x4 bits = __builtin_bit_cast(u32x4, v);
-    if constexpr (NT) {
-        if (((uintptr_t)p & 15u) == 0) { __builtin_nontemporal_store(bits, (gvec *)p); return; }
-    }
-    ((__attribute__((address_space(1))) LooseVec<4> *)p)->v = bits;
-}
-
-template <bool NT>
-__device__ __forceinline__ f32x4 load_state(const f32x4 *p)
-{
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
-}
-template <bool NT>
-__device__ __forceinline__ void store_state(f32x4 *p, f32x4 v)
-{
-    if constexpr (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
-}
-
-__device__ __forceinline__ float g_half_lo(uint32_t w)
-{
-    return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu));
-}
-__device__ __forceinline__ float g_half_hi(uint32_t w)
-{
-    return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16));
-}
-__device__ __forceinline__ bool g_nonfinite_f32(uint32_t w) { return (w & 0x7f800000u) == 0x7f800000u; }
-__device__ __forceinline__ bool g_nonfinite_f16x2(uint32_t w)
-{
-    return (((w & 0x7c007c00u) + 0x04000400u) & 0x80008000u) != 0u;
-}
-
-__device__ __forceinline__ void g_sgd(float g_sum, float c, float &x, float &v, float lr, float mu,
-                                      float wd)
-{
-    const float g = g_sum * c;
-    const float wx = wd * x;
-    const float d = g + wx;
-    const float mv = mu * v;
-    const float vn = mv + d;
-    const float lv = lr * vn;
-    v = vn;
-    x = x - lv;
+    if (view_dtype == XS_F32) *(__attribute__((address_space(1))) float *)(view + elem * 4) = x;
+    else *(__attribute__((address_space(1))) uint16_t *)(view + elem * 2) = to_half1(x, view_dtype);
 }
 
 struct GatherArgs {
@@ -103,33 +67,34 @@ struct GatherArgs {
     const float *x_in, *v_in;
     float *x_out, *v_out;
     const uintptr_t *param_ptrs;   // device [n_tensors] or nullptr
+    int view_dtype;                // dtype of the views param_ptrs point to
     float lr, mu, wd, c;
     int32_t *found_inf;
 };
 
 // The vector path for one lane.  `t` is either wave-uniform (scalar address loads) or per lane.
-// SHUF (fp16 gradients, whole wavefront in one tensor, complete row): lanes take state
-// vectors `lane` and `64 + lane` of the row instead of the two under their own gradient
+// EXCH (half-precision gradients, whole wavefront in one tensor, complete row): lanes take
+// state vectors `lane` and `64 + lane` of the row instead of the two under their own gradient
 // vector, and receive the matching gradient sums through the LDS crossbar, so that every
 // state access of the wavefront is one contiguous kilobyte.
-template <int W, bool F16, bool DETECT, bool VIEWS, bool NTG, bool NTS, bool NTX, bool SHUF>
+template <int W, int GT, bool DETECT, bool VIEWS, bool EXCH>
 __device__ __forceinline__ void vector_path(const GatherArgs &a, uint32_t t, uint64_t j, uint64_t k,
                                             bool &bad)
 {
-    constexpr int ES = F16 ? 2 : 4;
+    constexpr int ES = Grad<GT>::ES;
     constexpr int VEC = 16 / ES;
     constexpr int SV = VEC / 4;
     u32x4 g[W];
 #pragma unroll
     for (int w = 0; w < W; ++w)
-        g[w] = load_tensor_vec<NTG, ES>((const gbyte *)a.grad_ptrs[(uint64_t)t * W + w] + k * ES);
+        g[w] = load_tensor_vec<ES>((const gbyte *)a.grad_ptrs[(uint64_t)t * W + w] + k * ES);
     // state vector q of this lane starts at bucket element sj[q] = tensor element sk[q]
     uint64_t sj[SV], sk[SV];
 #pragma unroll
     for (int q = 0; q < SV; ++q) {
-        if constexpr (SHUF) {
+        if constexpr (EXCH) {
             const uint64_t lane_off = (uint64_t)threadIdx.x * VEC;       // j = row start + lane_off
-            const uint64_t d = (uint64_t)q * 4 * kLanes + 4 * threadIdx.x;
+            const uint64_t d = (uint64_t)q * 4 * kWave + 4 * threadIdx.x;
             sj[q] = j - lane_off + d;
             sk[q] = k - lane_off + d;
         } else {
@@ -140,73 +105,67 @@ __device__ __forceinline__ void vector_path(const GatherArgs &a, uint32_t t, uin
     f32x4 x[SV], v[SV];
 #pragma unroll
     for (int q = 0; q < SV; ++q) {
-        x[q] = load_state<NTX>((const f32x4 *)(a.x_in + sj[q]));
-        v[q] = load_state<NTX>((const f32x4 *)(a.v_in + sj[q]));
+        x[q] = load16f<true>((const f32x4 *)(a.x_in + sj[q]));
+        v[q] = load16f<true>((const f32x4 *)(a.v_in + sj[q]));
     }
     float s[VEC];
 #pragma unroll
-    for (int w = 0; w < W; ++w) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const uint32_t bits = g[w][q];
-            if constexpr (F16) {
-                if constexpr (DETECT) bad |= g_nonfinite_f16x2(bits);
-                const float lo = g_half_lo(bits), hi = g_half_hi(bits);
-                if (w == 0) { s[2 * q] = lo; s[2 * q + 1] = hi; }
-                else { s[2 * q] = s[2 * q] + lo; s[2 * q + 1] = s[2 * q + 1] + hi; }
-            } else {
-                if constexpr (DETECT) bad |= g_nonfinite_f32(bits);
-                const float f = __builtin_bit_cast(float, bits);
-                if (w == 0) s[q] = f;
-                else s[q] = s[q] + f;
-            }
-        }
-    }
-    if constexpr (SHUF) {
-        // element 4L+e of the row sits in lane L>>1, slot (L&1)*4+e; element 256+4L+e in lane
-        // 32+(L>>1), same slot
-        const int src0 = (int)((threadIdx.x >> 1) << 2);
-        const int src1 = (int)((32u + (threadIdx.x >> 1)) << 2);
-        const bool odd = (threadIdx.x & 1u) != 0u;
-        float t2[VEC];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int lo = __builtin_bit_cast(int, s[e]), hi = __builtin_bit_cast(int, s[4 + e]);
-            const int a_lo = __builtin_amdgcn_ds_bpermute(src0, lo);
-            const int a_hi = __builtin_amdgcn_ds_bpermute(src0, hi);
-            const int b_lo = __builtin_amdgcn_ds_bpermute(src1, lo);
-            const int b_hi = __builtin_amdgcn_ds_bpermute(src1, hi);
-            t2[e] = __builtin_bit_cast(float, odd ? a_hi : a_lo);
-            t2[4 + e] = __builtin_bit_cast(float, odd ? b_hi : b_lo);
-        }
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) s[e] = t2[e];
-    }
+    for (int w = 0; w < W; ++w) accumulate<GT, DETECT>(g[w], w == 0, s, bad);
+    if constexpr (EXCH) exchange_half_row(s);
 #pragma unroll
     for (int q = 0; q < SV; ++q) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             float xe = x[q][e], ve = v[q][e];
-            g_sgd(s[4 * q + e], a.c, xe, ve, a.lr, a.mu, a.wd);
+            sgd_update(s[4 * q + e], a.c, xe, ve, a.lr, a.mu, a.wd);
             x[q][e] = xe;
             v[q][e] = ve;
         }
-        store_state<NTS>((f32x4 *)(a.x_out + sj[q]), x[q]);
-        store_state<NTS>((f32x4 *)(a.v_out + sj[q]), v[q]);
+        store16f<true>((f32x4 *)(a.x_out + sj[q]), x[q]);
+        store16f<true>((f32x4 *)(a.v_out + sj[q]), v[q]);
     }
     if constexpr (VIEWS) {
-        gbyte *dst = (gbyte *)a.param_ptrs[t];
+        gbyte *view = (gbyte *)a.param_ptrs[t];
 #pragma unroll
-        for (int q = 0; q < SV; ++q) store_tensor_vec<NTS>(dst + sk[q] * 4, x[q]);
+        for (int q = 0; q < SV; ++q) store_view4(view, sk[q], x[q], a.view_dtype);
     }
 }
 
-template <int W, bool F16, bool DETECT, bool VIEWS, bool NTG, bool NTS, bool NTX>
-__global__ __launch_bounds__(kLanes) void gather_reduce_sgd_kernel(GatherArgs a)
+// One bucket element at a time: padding contributes +0, consecutive elements may belong to
+// different tensors.  `te` is carried along so that the search only ever moves forward.
+template <int GT, bool DETECT, bool VIEWS>
+__device__ __forceinline__ void element_path(const GatherArgs &a, uint32_t &te, uint64_t je, bool &bad)
 {
-    constexpr int ES = F16 ? 2 : 4;
-    constexpr int VEC = 16 / ES;
-    constexpr uint64_t ROW = (uint64_t)kLanes * VEC;
+    constexpr int ES = Grad<GT>::ES;
+    while (te + 1 < a.n_tensors && a.tb.offsets[te + 1] <= je) ++te;
+    const uint64_t ke = je - a.tb.offsets[te];
+    const bool valid = ke < a.tb.numel[te];
+    float s = 0.f;
+    if (valid) {
+        for (uint32_t w = 0; w < a.W; ++w) {
+            const gbyte *p = (const gbyte *)a.grad_ptrs[(uint64_t)te * a.W + w] + ke * ES;
+            uint32_t e;
+            if constexpr (Grad<GT>::HALF) e = *(const __attribute__((address_space(1))) uint16_t *)p;
+            else e = *(const __attribute__((address_space(1))) uint32_t *)p;
+            if constexpr (DETECT) bad |= Grad<GT>::nonfinite_elem(e);
+            const float f = Grad<GT>::lo(e);
+            s = (w == 0) ? f : s + f;
+        }
+    }
+    float xe = a.x_in[je], ve = a.v_in[je];
+    sgd_update(s, a.c, xe, ve, a.lr, a.mu, a.wd);
+    a.x_out[je] = xe;
+    a.v_out[je] = ve;
+    if constexpr (VIEWS) {
+        if (valid) store_view1((gbyte *)a.param_ptrs[te], ke, xe, a.view_dtype);
+    }
+}
+
+template <int W, int GT, bool DETECT, bool VIEWS>
+__global__ __launch_bounds__(kWave) void gather_reduce_sgd_kernel(GatherArgs a)
+{
+    constexpr int VEC = 16 / Grad<GT>::ES;
+    constexpr uint64_t ROW = (uint64_t)kWave * VEC;
     if (a.found_inf != nullptr && *(volatile int32_t *)a.found_inf != 0) return;
     bool bad = false;
 
@@ -224,47 +183,17 @@ __global__ __launch_bounds__(kLanes) void gather_reduce_sgd_kernel(GatherArgs a)
             // every active lane is a full vector of tensor t_row: scalar address loads
             const uint32_t tu = (uint32_t)__builtin_amdgcn_readfirstlane((int)t_row);
             const uint64_t ku = j - a.tb.offsets[tu];
-            if (F16 && (row + 1) * ROW <= a.n_bucket)      // complete row: all 64 lanes are here
-                vector_path<W, F16, DETECT, VIEWS, NTG, NTS, NTX, F16>(a, tu, j, ku, bad);
+            if (Grad<GT>::HALF && (row + 1) * ROW <= a.n_bucket)      // complete row: all 64 lanes here
+                vector_path<W, GT, DETECT, VIEWS, Grad<GT>::HALF>(a, tu, j, ku, bad);
             else
-                vector_path<W, F16, DETECT, VIEWS, NTG, NTS, NTX, false>(a, tu, j, ku, bad);
+                vector_path<W, GT, DETECT, VIEWS, false>(a, tu, j, ku, bad);
         } else if (full) {
-            vector_path<W, F16, DETECT, VIEWS, NTG, NTS, NTX, false>(a, t, j, k, bad);
+            vector_path<W, GT, DETECT, VIEWS, false>(a, t, j, k, bad);
         } else {
-            // element by element: padding contributes +0, elements may belong to later tensors
             uint32_t te = t;
             for (int e = 0; e < VEC; ++e) {
-                const uint64_t je = j + e;
-                if (je >= a.n_bucket) break;
-                while (te + 1 < a.n_tensors && a.tb.offsets[te + 1] <= je) ++te;
-                const uint64_t ke = je - a.tb.offsets[te];
-                const bool valid = ke < a.tb.numel[te];
-                float s = 0.f;
-                if (valid) {
-#pragma unroll
-                    for (int w = 0; w < W; ++w) {
-                        const gbyte *p = (const gbyte *)a.grad_ptrs[(uint64_t)te * W + w] + ke * ES;
-                        float f;
-                        if constexpr (F16) {
-                            const uint16_t h = *(const __attribute__((address_space(1))) uint16_t *)p;
-                            if constexpr (DETECT) bad |= (h & 0x7c00u) == 0x7c00u;
-                            f = (float)__builtin_bit_cast(_Float16, h);
-                        } else {
-                            const uint32_t b = *(const __attribute__((address_space(1))) uint32_t *)p;
-                            if constexpr (DETECT) bad |= g_nonfinite_f32(b);
-                            f = __builtin_bit_cast(float, b);
-                        }
-                        s = (w == 0) ? f : s + f;
-                    }
-                }
-                float xe = a.x_in[je], ve = a.v_in[je];
-                g_sgd(s, a.c, xe, ve, a.lr, a.mu, a.wd);
-                a.x_out[je] = xe;
-                a.v_out[je] = ve;
-                if constexpr (VIEWS) {
-                    if (valid)
-                        *(__attribute__((address_space(1))) float *)((gbyte *)a.param_ptrs[te] + ke * 4) = xe;
-                }
+                if (j + e >= a.n_bucket) break;
+                element_path<GT, DETECT, VIEWS>(a, te, j + e, bad);
             }
         }
     }
@@ -275,13 +204,12 @@ __global__ __launch_bounds__(kLanes) void gather_reduce_sgd_kernel(GatherArgs a)
     }
 }
 
-// Any W: replicas accumulated one after the other (run-time trip count).
-template <bool F16, bool DETECT, bool VIEWS>
-__global__ __launch_bounds__(kLanes) void gather_reduce_sgd_anyw_kernel(GatherArgs a)
+// Any W: element by element with a run-time replica count.
+template <int GT, bool DETECT, bool VIEWS>
+__global__ __launch_bounds__(kWave) void gather_reduce_sgd_anyw_kernel(GatherArgs a)
 {
-    constexpr int ES = F16 ? 2 : 4;
-    constexpr int VEC = 16 / ES;
-    constexpr uint64_t ROW = (uint64_t)kLanes * VEC;
+    constexpr int VEC = 16 / Grad<GT>::ES;
+    constexpr uint64_t ROW = (uint64_t)kWave * VEC;
     if (a.found_inf != nullptr && *(volatile int32_t *)a.found_inf != 0) return;
     bool bad = false;
     for (uint64_t row = blockIdx.x; row < a.n_rows; row += gridDim.x) {
@@ -289,36 +217,8 @@ __global__ __launch_bounds__(kLanes) void gather_reduce_sgd_anyw_kernel(GatherAr
         if (j >= a.n_bucket) continue;
         uint32_t te = a.tb.row_first[row];
         for (int e = 0; e < VEC; ++e) {
-            const uint64_t je = j + e;
-            if (je >= a.n_bucket) break;
-            while (te + 1 < a.n_tensors && a.tb.offsets[te + 1] <= je) ++te;
-            const uint64_t ke = je - a.tb.offsets[te];
-            const bool valid = ke < a.tb.numel[te];
-            float s = 0.f;
-            if (valid) {
-                for (uint32_t w = 0; w < a.W; ++w) {
-                    const gbyte *p = (const gbyte *)a.grad_ptrs[(uint64_t)te * a.W + w] + ke * ES;
-                    float f;
-                    if constexpr (F16) {
-                        const uint16_t h = *(const __attribute__((address_space(1))) uint16_t *)p;
-                        if constexpr (DETECT) bad |= (h & 0x7c00u) == 0x7c00u;
-                        f = (float)__builtin_bit_cast(_Float16, h);
-                    } else {
-                        const uint32_t b = *(const __attribute__((address_space(1))) uint32_t *)p;
-                        if constexpr (DETECT) bad |= g_nonfinite_f32(b);
-                        f = __builtin_bit_cast(float, b);
-                    }
-                    s = (w == 0) ? f : s + f;
-                }
-            }
-            float xe = a.x_in[je], ve = a.v_in[je];
-            g_sgd(s, a.c, xe, ve, a.lr, a.mu, a.wd);
-            a.x_out[je] = xe;
-            a.v_out[je] = ve;
-            if constexpr (VIEWS) {
-                if (valid)
-                    *(__attribute__((address_space(1))) float *)((gbyte *)a.param_ptrs[te] + ke * 4) = xe;
-            }
+            if (j + e >= a.n_bucket) break;
+            element_path<GT, DETECT, VIEWS>(a, te, j + e, bad);
         }
     }
     if constexpr (DETECT) {
@@ -328,49 +228,51 @@ __global__ __launch_bounds__(kLanes) void gather_reduce_sgd_anyw_kernel(GatherAr
 }
 
 // ---- dispatch ---------------------------------------------------------------------------
-template <int W, bool F16, bool DETECT, bool VIEWS>
-static void launch_g(const GatherArgs &a, dim3 grid, unsigned lds, hipStream_t stream)
+template <int W, int GT>
+static void launch_g(const GatherArgs &a, bool detect, bool views, dim3 grid, unsigned lds,
+                     hipStream_t stream)
 {
-    // cache hints as in the bucket form: every stream non-temporal
-    hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, F16, DETECT, VIEWS, true, true, true>), grid,
-                       dim3(kLanes), lds, stream, a);
+    if (detect)
+        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, true, false>), grid, dim3(kWave), lds, stream, a);
+    else if (views)
+        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, false, true>), grid, dim3(kWave), lds, stream, a);
+    else
+        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, false, false>), grid, dim3(kWave), lds, stream, a);
 }
 
-template <int W>
-static void launch_gw(const GatherArgs &a, bool f16, bool detect, bool views, dim3 grid,
-                      unsigned lds, hipStream_t stream)
-{
-    if (f16) {
-        if (detect) launch_g<W, true, true, false>(a, grid, lds, stream);
-        else if (views) launch_g<W, true, false, true>(a, grid, lds, stream);
-        else launch_g<W, true, false, false>(a, grid, lds, stream);
-    } else {
-        if (detect) launch_g<W, false, true, false>(a, grid, lds, stream);
-        else if (views) launch_g<W, false, false, true>(a, grid, lds, stream);
-        else launch_g<W, false, false, false>(a, grid, lds, stream);
-    }
-}
-
-template <bool F16>
+template <int GT>
 static void launch_ganyw(const GatherArgs &a, bool detect, bool views, dim3 grid, unsigned lds,
                          hipStream_t stream)
 {
     if (detect)
-        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<F16, true, false>), grid, dim3(kLanes), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, true, false>), grid, dim3(kWave), lds, stream, a);
     else if (views)
-        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<F16, false, true>), grid, dim3(kLanes), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, false, true>), grid, dim3(kWave), lds, stream, a);
     else
-        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<F16, false, false>), grid, dim3(kLanes), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, false, false>), grid, dim3(kWave), lds, stream, a);
+}
+
+template <int GT>
+static void launch_gt(const GatherArgs &a, bool detect, bool views, dim3 grid, unsigned lds,
+                      hipStream_t stream)
+{
+    switch (a.W) {
+    case 2: launch_g<2, GT>(a, detect, views, grid, lds, stream); break;
+    case 4: launch_g<4, GT>(a, detect, views, grid, lds, stream); break;
+    case 8: launch_g<8, GT>(a, detect, views, grid, lds, stream); break;
+    case 16: launch_g<16, GT>(a, detect, views, grid, lds, stream); break;
+    default: launch_ganyw<GT>(a, detect, views, grid, lds, stream); break;
+    }
 }
 
 int launch_gather_reduce_sgd(const xs_plan *plan, const void *const *grad_ptrs, uint32_t W,
                              const float *x_in, const float *v_in, float *x_out, float *v_out,
-                             void *const *param_ptrs, const xs_sgd_hparams &hp,
+                             void *const *param_ptrs, int view_dtype, const xs_sgd_hparams &hp,
                              int32_t *found_inf, bool detect, hipStream_t stream)
 {
     const int cus = compute_units();
     if (cus < 0) return cus;
-    const bool f16 = plan->dtype == XS_F16;
+    const bool half = plan->dtype != XS_F32;
     GatherArgs a;
     a.tb = plan->tables;
     a.n_tensors = plan->n_tensors;
@@ -380,6 +282,7 @@ int launch_gather_reduce_sgd(const xs_plan *plan, const void *const *grad_ptrs, 
     a.grad_ptrs = (const uintptr_t *)grad_ptrs;
     a.x_in = x_in; a.v_in = v_in; a.x_out = x_out; a.v_out = v_out;
     a.param_ptrs = (const uintptr_t *)param_ptrs;
+    a.view_dtype = view_dtype;
     a.lr = hp.lr; a.mu = hp.momentum; a.wd = hp.weight_decay;
     volatile float one_over_w = 1.0f / (float)W;
     a.c = hp.inv_loss_scale * one_over_w;
@@ -395,20 +298,15 @@ int launch_gather_reduce_sgd(const xs_plan *plan, const void *const *grad_ptrs, 
     if (blocks > 0x7fffffffull) blocks = 0x7fffffffull;
     const dim3 grid((unsigned)blocks);
     // the address look-ups in front of the loads want about twice the residency of the
-    // bucket form: 20 one-wave workgroups per compute unit for fp32, 10 for fp16 (measured)
-    const int lds_auto = f16 ? 16384 : 8192;
+    // bucket form: 20 one-wave workgroups per compute unit for fp32, 10 for half precision
+    const int lds_auto = half ? 16384 : 8192;
     const unsigned lds = (unsigned)(g_tuning.gather_lds_reserve < 0 ? lds_auto : g_tuning.gather_lds_reserve);
     const bool views = param_ptrs != nullptr;
 
-    switch (W) {
-    case 1: launch_gw<1>(a, f16, detect, views, grid, lds, stream); break;
-    case 2: launch_gw<2>(a, f16, detect, views, grid, lds, stream); break;
-    case 4: launch_gw<4>(a, f16, detect, views, grid, lds, stream); break;
-    case 8: launch_gw<8>(a, f16, detect, views, grid, lds, stream); break;
-    case 16: launch_gw<16>(a, f16, detect, views, grid, lds, stream); break;
-    default:
-        if (f16) launch_ganyw<true>(a, detect, views, grid, lds, stream);
-        else launch_ganyw<false>(a, detect, views, grid, lds, stream);
+    switch (plan->dtype) {
+    case XS_F16: launch_gt<XS_F16>(a, detect, views, grid, lds, stream); break;
+    case XS_BF16: launch_gt<XS_BF16>(a, detect, views, grid, lds, stream); break;
+    default: launch_gt<XS_F32>(a, detect, views, grid, lds, stream); break;
     }
     XS_HIP_TRY(hipGetLastError());
     return XS_OK;

@@ -25,18 +25,16 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 int compute_units();   // > 0, or a negative xs_status
 
 // ---- tuning ---------------------------------------------------------------------
-struct Tuning {
-    int reduce_wg_per_cu;   // 0: one vector per thread, no loop
+struct Tuning {              // indexed by xs_tuning_key
+    int reduce_wg_per_cu;     // 0: one vector per lane, no loop
     int copy_wg_per_cu;
-    int nt_loads;
-    int nt_stores;
-    int nt_state_loads;
-    int reduce_lds_reserve;   // bytes of LDS reserved per reduce workgroup (occupancy throttle)
+    int nt_grads;             // non-temporal loads of gradient replicas
+    int nt_state;             // non-temporal loads and stores of parameters and momentum
+    int reduce_lds_reserve;   // bytes of LDS reserved per reduce workgroup (-1: per dtype)
     int reduce_max_wg;        // absolute cap on reduce workgroups (0 = none): background pacing
     int copy_max_wg;          // absolute cap on pack/unpack workgroups (0 = none)
     int copy_nt;              // non-temporal loads and stores in pack/unpack
     int gather_lds_reserve;   // as reduce_lds_reserve, for the gathering form
-    int f16_state_shuffle;    // fp16 gradients: contiguous state vectors per wavefront (see kernel)
 };
 extern Tuning g_tuning;
 
@@ -84,10 +82,10 @@ int launch_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_p
                   hipStream_t stream);
 int launch_gather_reduce_sgd(const xs_plan *plan, const void *const *grad_ptrs, uint32_t W,
                              const float *x_in, const float *v_in, float *x_out, float *v_out,
-                             void *const *param_ptrs, const xs_sgd_hparams &hp,
+                             void *const *param_ptrs, int view_dtype, const xs_sgd_hparams &hp,
                              int32_t *found_inf, bool detect, hipStream_t stream);
 int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64_t n,
                       const float *x_in, const float *v_in, float *x_out, float *v_out,
                       const xs_sgd_hparams &hp, int32_t *found_inf, bool detect,
-                      hipStream_t stream);
+                      void *model_copy, int model_copy_dtype, hipStream_t stream);
 }  // namespace xs

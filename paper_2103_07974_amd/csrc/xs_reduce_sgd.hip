@@ -18,352 +18,230 @@
 //    fp32 state accesses of a wavefront are contiguous (see the main loop).
 //  * The only cross-lane quantity besides that is the overflow flag: a wavefront ballot, then
 //    one atomic per wavefront that saw a non-finite gradient.
+#include "xs_device.h"
 #include "xs_internal.h"
 
 namespace xs {
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kThreads = 64;   // one wavefront per workgroup: finest dispatch grain
+constexpr int kThreads = kWave;   // one wavefront per workgroup: finest dispatch grain
 
 template <int N>
 struct ReplicaPtrs {
     const void *p[N];
 };
 
-template <bool NT>
-__device__ __forceinline__ u32x4 load_g(const u32x4 *p)
+struct ReduceArgs {
+    uint64_t n;
+    const float *x_in, *v_in;
+    float *x_out, *v_out;
+    float lr, mu, wd, c;
+    int32_t *found_inf;
+    void *model_copy;       // half-precision copy of the updated parameters, or nullptr
+    int model_copy_dtype;   // XS_F16 or XS_BF16
+};
+
+// One element of the ragged tail (fewer than VEC elements at the end of the bucket).
+template <int GT, bool DETECT, typename Reps>
+__device__ __forceinline__ void tail_element(const Reps &reps, uint32_t W, const ReduceArgs &a,
+                                             uint64_t j, bool &bad)
 {
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
+    float s = 0.f;
+    for (uint32_t w = 0; w < W; ++w) {
+        uint32_t e;
+        if constexpr (Grad<GT>::HALF) e = ((const uint16_t *)reps.p[w])[j];
+        else e = ((const uint32_t *)reps.p[w])[j];
+        if constexpr (DETECT) bad |= Grad<GT>::nonfinite_elem(e);
+        const float f = Grad<GT>::lo(e);
+        s = (w == 0) ? f : s + f;
+    }
+    float xe = a.x_in[j], ve = a.v_in[j];
+    sgd_update(s, a.c, xe, ve, a.lr, a.mu, a.wd);
+    a.x_out[j] = xe;
+    a.v_out[j] = ve;
+    if (a.model_copy) ((uint16_t *)a.model_copy)[j] = to_half1(xe, a.model_copy_dtype);
 }
 
-template <bool NT>
-__device__ __forceinline__ f32x4 load_s(const f32x4 *p)
-{
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
-}
-
-template <bool NT>
-__device__ __forceinline__ void store_s(f32x4 *p, f32x4 v)
-{
-    if constexpr (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
-}
-
-__device__ __forceinline__ float half_lo(uint32_t w)
-{
-    return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu));
-}
-__device__ __forceinline__ float half_hi(uint32_t w)
-{
-    return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16));
-}
-
-// non-finite tests on raw bits: exponent field all ones
-__device__ __forceinline__ bool nonfinite_f32(uint32_t w) { return (w & 0x7f800000u) == 0x7f800000u; }
-__device__ __forceinline__ bool nonfinite_f16x2(uint32_t w)
-{
-    // adding one exponent step carries into bit 15 only from an all-ones exponent
-    return (((w & 0x7c007c00u) + 0x04000400u) & 0x80008000u) != 0u;
-}
-
-__device__ __forceinline__ void sgd(float g_sum, float c, float &x, float &v, float lr, float mu,
-                                    float wd)
-{
-    const float g = g_sum * c;
-    const float wx = wd * x;
-    const float d = g + wx;
-    const float mv = mu * v;
-    const float vn = mv + d;
-    const float lv = lr * vn;
-    v = vn;
-    x = x - lv;
-}
-
-// VEC elements per lane per trip: 4 (fp32 gradients) or 8 (fp16 gradients), so that
+// VEC elements per lane per trip: 4 (fp32 gradients) or 8 (fp16 / bf16 gradients), so that
 // every gradient load is 16 bytes wide.
-template <int W, bool F16, bool DETECT, bool NTL, bool NTS, bool NTX, bool SHUF>
-__global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(
-    ReplicaPtrs<W> reps, uint64_t n, const float *x_in, const float *v_in,
-    float *x_out, float *v_out, float lr, float mu, float wd, float c,
-    int32_t *found_inf)
+template <int W, int GT, bool DETECT, bool NTG, bool NTS>
+__global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(ReplicaPtrs<W> reps, ReduceArgs a)
 {
-    constexpr int VEC = F16 ? 8 : 4;
+    constexpr bool HALF = Grad<GT>::HALF;
+    constexpr int VEC = 16 / Grad<GT>::ES;
     constexpr int SV = VEC / 4;   // fp32 state vectors per gradient vector
-    if (found_inf != nullptr && *(volatile int32_t *)found_inf != 0) return;
+    if (a.found_inf != nullptr && *(volatile int32_t *)a.found_inf != 0) return;
 
-    const uint64_t nvec = n / VEC;
+    const uint64_t nvec = a.n / VEC;
     const uint64_t stride = (uint64_t)gridDim.x * kThreads;
     bool bad = false;
 
     for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
         u32x4 g[W];
 #pragma unroll
-        for (int w = 0; w < W; ++w) g[w] = load_g<NTL>((const u32x4 *)reps.p[w] + i);
+        for (int w = 0; w < W; ++w) g[w] = load16<NTG>((const u32x4 *)reps.p[w] + i);
         // Which fp32 state vectors this lane updates.  fp32 gradients: the one under its
-        // gradient vector.  fp16 gradients: a lane's 8 elements would be two neighbouring state
-        // vectors, i.e. 32-byte strides per load instruction; in a full row of 64 lanes the
-        // lanes instead take state vectors `lane` and `64 + lane` of the row, so that every
-        // state load and store of the wavefront is one contiguous kilobyte, and the gradient
-        // sums are moved to the owning lanes through the LDS crossbar afterwards.
+        // gradient vector.  Half-precision gradients: a lane's 8 elements would be two
+        // neighbouring state vectors, i.e. 32-byte strides per load instruction; in a full row
+        // of 64 lanes the lanes instead take state vectors `lane` and `64 + lane` of the row,
+        // so that every state load and store of the wavefront is one contiguous kilobyte, and
+        // the gradient sums are moved to the owning lanes through the LDS crossbar afterwards.
         uint64_t sx[SV];
-        bool shuffled = false;
-        if constexpr (F16) {
-            const uint64_t row0 = i - threadIdx.x;            // vector index of lane 0 (kThreads == 64)
-            shuffled = SHUF && row0 + (kThreads - 1) < nvec;   // uniform: every lane of the row is live
-            sx[0] = shuffled ? row0 * 2 + threadIdx.x : i * 2;
-            sx[1] = shuffled ? row0 * 2 + kThreads + threadIdx.x : i * 2 + 1;
+        bool exchanged = false;
+        if constexpr (HALF) {
+            const uint64_t row0 = i - threadIdx.x;                 // vector index of lane 0
+            exchanged = row0 + (kThreads - 1) < nvec;              // uniform: the whole row is live
+            sx[0] = exchanged ? row0 * 2 + threadIdx.x : i * 2;
+            sx[1] = exchanged ? row0 * 2 + kThreads + threadIdx.x : i * 2 + 1;
         } else {
             sx[0] = i;
         }
         f32x4 x[SV], v[SV];
 #pragma unroll
         for (int k = 0; k < SV; ++k) {
-            x[k] = load_s<NTX>((const f32x4 *)x_in + sx[k]);
-            v[k] = load_s<NTX>((const f32x4 *)v_in + sx[k]);
+            x[k] = load16f<NTS>((const f32x4 *)a.x_in + sx[k]);
+            v[k] = load16f<NTS>((const f32x4 *)a.v_in + sx[k]);
         }
         float s[VEC];
 #pragma unroll
-        for (int w = 0; w < W; ++w) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t bits = g[w][q];
-                if constexpr (F16) {
-                    if constexpr (DETECT) bad |= nonfinite_f16x2(bits);
-                    const float lo = half_lo(bits), hi = half_hi(bits);
-                    if (w == 0) { s[2 * q] = lo; s[2 * q + 1] = hi; }
-                    else { s[2 * q] = s[2 * q] + lo; s[2 * q + 1] = s[2 * q + 1] + hi; }
-                } else {
-                    if constexpr (DETECT) bad |= nonfinite_f32(bits);
-                    const float f = __builtin_bit_cast(float, bits);
-                    if (w == 0) s[q] = f;
-                    else s[q] = s[q] + f;
-                }
-            }
-        }
-        if constexpr (F16) {
-            if (shuffled) {
-                // element 4L+e of the row sits in lane L>>1, slot (L&1)*4+e; element 256+4L+e in
-                // lane 32+(L>>1), same slot
-                const int src0 = (int)((threadIdx.x >> 1) << 2);
-                const int src1 = (int)((32u + (threadIdx.x >> 1)) << 2);
-                const bool odd = (threadIdx.x & 1u) != 0u;
-                float t[VEC];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int lo = __builtin_bit_cast(int, s[e]), hi = __builtin_bit_cast(int, s[4 + e]);
-                    const int a_lo = __builtin_amdgcn_ds_bpermute(src0, lo);
-                    const int a_hi = __builtin_amdgcn_ds_bpermute(src0, hi);
-                    const int b_lo = __builtin_amdgcn_ds_bpermute(src1, lo);
-                    const int b_hi = __builtin_amdgcn_ds_bpermute(src1, hi);
-                    t[e] = __builtin_bit_cast(float, odd ? a_hi : a_lo);
-                    t[4 + e] = __builtin_bit_cast(float, odd ? b_hi : b_lo);
-                }
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) s[e] = t[e];
-            }
+        for (int w = 0; w < W; ++w) accumulate<GT, DETECT>(g[w], w == 0, s, bad);
+        if constexpr (HALF) {
+            if (exchanged) exchange_half_row(s);
         }
 #pragma unroll
         for (int k = 0; k < SV; ++k) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 float xe = x[k][q], ve = v[k][q];
-                sgd(s[4 * k + q], c, xe, ve, lr, mu, wd);
+                sgd_update(s[4 * k + q], a.c, xe, ve, a.lr, a.mu, a.wd);
                 x[k][q] = xe;
                 v[k][q] = ve;
             }
-            store_s<NTS>((f32x4 *)x_out + sx[k], x[k]);
-            store_s<NTS>((f32x4 *)v_out + sx[k], v[k]);
+            store16f<NTS>((f32x4 *)a.x_out + sx[k], x[k]);
+            store16f<NTS>((f32x4 *)a.v_out + sx[k], v[k]);
+            if (a.model_copy)
+                store8<NTS>((u32x2 *)a.model_copy + sx[k], to_half4(x[k], a.model_copy_dtype));
         }
     }
 
     // ragged tail: fewer than VEC elements, one lane each, in workgroup 0
-    const uint32_t rem = (uint32_t)(n - nvec * VEC);
-    if (blockIdx.x == 0 && threadIdx.x < rem) {
-        const uint64_t j = nvec * VEC + threadIdx.x;
-        float s = 0.f;
-#pragma unroll
-        for (int w = 0; w < W; ++w) {
-            float f;
-            if constexpr (F16) {
-                const uint16_t h = ((const uint16_t *)reps.p[w])[j];
-                if constexpr (DETECT) bad |= (h & 0x7c00u) == 0x7c00u;
-                f = (float)__builtin_bit_cast(_Float16, h);
-            } else {
-                const uint32_t b = ((const uint32_t *)reps.p[w])[j];
-                if constexpr (DETECT) bad |= nonfinite_f32(b);
-                f = __builtin_bit_cast(float, b);
-            }
-            s = (w == 0) ? f : s + f;
-        }
-        float xe = x_in[j], ve = v_in[j];
-        sgd(s, c, xe, ve, lr, mu, wd);
-        x_out[j] = xe;
-        v_out[j] = ve;
-    }
+    const uint32_t rem = (uint32_t)(a.n - nvec * VEC);
+    if (blockIdx.x == 0 && threadIdx.x < rem)
+        tail_element<GT, DETECT>(reps, (uint32_t)W, a, nvec * VEC + threadIdx.x, bad);
 
     if constexpr (DETECT) {
         // wavefront-level vote, then at most one atomic per wavefront
         if (__builtin_amdgcn_ballot_w64(bad) != 0ull && (threadIdx.x & 63u) == 0u)
-            atomicOr(found_inf, 1);
+            atomicOr(a.found_inf, 1);
     }
 }
 
-// Any W up to XS_MAX_REPLICAS: replica loop with a run-time trip count, four loads
-// in flight at a time.  Same arithmetic and order as the specialised kernels.
-template <bool F16, bool DETECT>
+// Any W up to XS_MAX_REPLICAS: replica loop with a run-time trip count, four loads in flight
+// at a time.  Same arithmetic and order as the specialised kernels; plain lane mapping.
+template <int GT, bool DETECT>
 __global__ __launch_bounds__(kThreads) void reduce_sgd_anyw_kernel(
-    ReplicaPtrs<XS_MAX_REPLICAS> reps, uint32_t W, uint64_t n, const float *x_in,
-    const float *v_in, float *x_out, float *v_out, float lr,
-    float mu, float wd, float c, int32_t *found_inf)
+    ReplicaPtrs<XS_MAX_REPLICAS> reps, uint32_t W, ReduceArgs a)
 {
-    constexpr int VEC = F16 ? 8 : 4;
-    if (found_inf != nullptr && *(volatile int32_t *)found_inf != 0) return;
-    const uint64_t stride = (uint64_t)gridDim.x * kThreads * VEC;
+    constexpr int ES = Grad<GT>::ES;
+    constexpr int VEC = 16 / ES;
+    constexpr int SV = VEC / 4;
+    if (a.found_inf != nullptr && *(volatile int32_t *)a.found_inf != 0) return;
+    const uint64_t nvec = a.n / VEC;
+    const uint64_t stride = (uint64_t)gridDim.x * kThreads;
     bool bad = false;
-    // element-granular with a guarded last vector: simple, and only used for unusual W
-    for (uint64_t base = ((uint64_t)blockIdx.x * kThreads + threadIdx.x) * VEC; base < n;
-         base += stride) {
-        const int cnt = (n - base) < (uint64_t)VEC ? (int)(n - base) : VEC;
+    for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
         float s[VEC];
-        if (cnt == VEC) {
-            const uint64_t byte_off = base * (F16 ? 2 : 4);
-            {
-                const u32x4 g = *(const u32x4 *)((const char *)reps.p[0] + byte_off);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const uint32_t bits = g[q];   // a scalar copy: bit_cast of a vector element misreads
-                    if constexpr (F16) {
-                        if constexpr (DETECT) bad |= nonfinite_f16x2(bits);
-                        s[2 * q] = half_lo(bits);
-                        s[2 * q + 1] = half_hi(bits);
-                    } else {
-                        if constexpr (DETECT) bad |= nonfinite_f32(bits);
-                        s[q] = __builtin_bit_cast(float, bits);
-                    }
-                }
-            }
+        accumulate<GT, DETECT>(*((const u32x4 *)reps.p[0] + i), true, s, bad);
 #pragma unroll 4
-            for (uint32_t w = 1; w < W; ++w) {
-                const u32x4 g = *(const u32x4 *)((const char *)reps.p[w] + byte_off);
+        for (uint32_t w = 1; w < W; ++w)
+            accumulate<GT, DETECT>(*((const u32x4 *)reps.p[w] + i), false, s, bad);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const uint32_t bits = g[q];
-                    if constexpr (F16) {
-                        if constexpr (DETECT) bad |= nonfinite_f16x2(bits);
-                        s[2 * q] = s[2 * q] + half_lo(bits);
-                        s[2 * q + 1] = s[2 * q + 1] + half_hi(bits);
-                    } else {
-                        if constexpr (DETECT) bad |= nonfinite_f32(bits);
-                        s[q] = s[q] + __builtin_bit_cast(float, bits);
-                    }
-                }
+        for (int k = 0; k < SV; ++k) {
+            f32x4 x = ((const f32x4 *)a.x_in)[i * SV + k], v = ((const f32x4 *)a.v_in)[i * SV + k];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float xe = x[q], ve = v[q];
+                sgd_update(s[4 * k + q], a.c, xe, ve, a.lr, a.mu, a.wd);
+                x[q] = xe;
+                v[q] = ve;
             }
-        } else {
-            for (int e = 0; e < cnt; ++e) {
-                float acc = 0.f;
-                for (uint32_t w = 0; w < W; ++w) {
-                    float f;
-                    if constexpr (F16) {
-                        const uint16_t h = ((const uint16_t *)reps.p[w])[base + e];
-                        if constexpr (DETECT) bad |= (h & 0x7c00u) == 0x7c00u;
-                        f = (float)__builtin_bit_cast(_Float16, h);
-                    } else {
-                        const uint32_t b = ((const uint32_t *)reps.p[w])[base + e];
-                        if constexpr (DETECT) bad |= nonfinite_f32(b);
-                        f = __builtin_bit_cast(float, b);
-                    }
-                    acc = (w == 0) ? f : acc + f;
-                }
-                s[e] = acc;
-            }
-        }
-        for (int e = 0; e < cnt; ++e) {
-            float xe = x_in[base + e], ve = v_in[base + e];
-            sgd(s[e], c, xe, ve, lr, mu, wd);
-            x_out[base + e] = xe;
-            v_out[base + e] = ve;
+            ((f32x4 *)a.x_out)[i * SV + k] = x;
+            ((f32x4 *)a.v_out)[i * SV + k] = v;
+            if (a.model_copy) ((u32x2 *)a.model_copy)[i * SV + k] = to_half4(x, a.model_copy_dtype);
         }
     }
+    const uint32_t rem = (uint32_t)(a.n - nvec * VEC);
+    if (blockIdx.x == 0 && threadIdx.x < rem)
+        tail_element<GT, DETECT>(reps, W, a, nvec * VEC + threadIdx.x, bad);
     if constexpr (DETECT) {
         if (__builtin_amdgcn_ballot_w64(bad) != 0ull && (threadIdx.x & 63u) == 0u)
-            atomicOr(found_inf, 1);
+            atomicOr(a.found_inf, 1);
     }
 }
 
 // ---- dispatch --------------------------------------------------------------------
-struct LaunchArgs {
+struct Launch {
     const void *const *replicas;
-    uint64_t n;
-    const float *x_in, *v_in;
-    float *x_out, *v_out;
-    float lr, mu, wd, c;
-    int32_t *found_inf;
+    ReduceArgs a;
     dim3 grid;
     unsigned lds_reserve;
-    bool shuffle;
     hipStream_t stream;
 };
 
-template <int W, bool F16, bool DETECT, bool NTL, bool NTS, bool NTX>
-static void launch_one(const LaunchArgs &a)
+template <int W, int GT, bool DETECT, bool NTG, bool NTS>
+static void launch_one(const Launch &l)
 {
     ReplicaPtrs<W> r;
-    for (int w = 0; w < W; ++w) r.p[w] = a.replicas[w];
-    if (F16 && a.shuffle)
-        hipLaunchKernelGGL((reduce_sgd_kernel<W, F16, DETECT, NTL, NTS, NTX, F16>), a.grid,
-                           dim3(kThreads), a.lds_reserve, a.stream, r, a.n, a.x_in, a.v_in, a.x_out,
-                           a.v_out, a.lr, a.mu, a.wd, a.c, a.found_inf);
-    else
-        hipLaunchKernelGGL((reduce_sgd_kernel<W, F16, DETECT, NTL, NTS, NTX, false>), a.grid,
-                           dim3(kThreads), a.lds_reserve, a.stream, r, a.n, a.x_in, a.v_in, a.x_out,
-                           a.v_out, a.lr, a.mu, a.wd, a.c, a.found_inf);
+    for (int w = 0; w < W; ++w) r.p[w] = l.replicas[w];
+    hipLaunchKernelGGL((reduce_sgd_kernel<W, GT, DETECT, NTG, NTS>), l.grid, dim3(kThreads),
+                       l.lds_reserve, l.stream, r, l.a);
 }
 
-template <int W, bool F16, bool DETECT>
-static void launch_nt(const LaunchArgs &a, int nt)
+template <int W, int GT, bool DETECT>
+static void launch_nt(const Launch &l, bool ntg, bool nts)
 {
-    switch (nt & 7) {
-    case 0: launch_one<W, F16, DETECT, false, false, false>(a); break;
-    case 1: launch_one<W, F16, DETECT, true, false, false>(a); break;
-    case 2: launch_one<W, F16, DETECT, false, true, false>(a); break;
-    case 3: launch_one<W, F16, DETECT, true, true, false>(a); break;
-    case 4: launch_one<W, F16, DETECT, false, false, true>(a); break;
-    case 5: launch_one<W, F16, DETECT, true, false, true>(a); break;
-    case 6: launch_one<W, F16, DETECT, false, true, true>(a); break;
-    default: launch_one<W, F16, DETECT, true, true, true>(a); break;
-    }
+    if (ntg) { if (nts) launch_one<W, GT, DETECT, true, true>(l); else launch_one<W, GT, DETECT, true, false>(l); }
+    else     { if (nts) launch_one<W, GT, DETECT, false, true>(l); else launch_one<W, GT, DETECT, false, false>(l); }
+}
+
+template <int W, int GT>
+static void launch_gt(const Launch &l, bool detect, bool ntg, bool nts)
+{
+    if (detect) launch_nt<W, GT, true>(l, ntg, nts);
+    else launch_nt<W, GT, false>(l, ntg, nts);
 }
 
 template <int W>
-static void launch_w(const LaunchArgs &a, bool f16, bool detect, int nt)
+static void launch_w(const Launch &l, int dtype, bool detect, bool ntg, bool nts)
 {
-    if (f16) { if (detect) launch_nt<W, true, true>(a, nt); else launch_nt<W, true, false>(a, nt); }
-    else     { if (detect) launch_nt<W, false, true>(a, nt); else launch_nt<W, false, false>(a, nt); }
+    switch (dtype) {
+    case XS_F16: launch_gt<W, XS_F16>(l, detect, ntg, nts); break;
+    case XS_BF16: launch_gt<W, XS_BF16>(l, detect, ntg, nts); break;
+    default: launch_gt<W, XS_F32>(l, detect, ntg, nts); break;
+    }
 }
 
-template <bool F16, bool DETECT>
-static void launch_anyw(const LaunchArgs &a, uint32_t W)
+template <int GT>
+static void launch_anyw(const Launch &l, uint32_t W, bool detect)
 {
     ReplicaPtrs<XS_MAX_REPLICAS> r;
-    for (uint32_t w = 0; w < XS_MAX_REPLICAS; ++w) r.p[w] = w < W ? a.replicas[w] : nullptr;
-    hipLaunchKernelGGL((reduce_sgd_anyw_kernel<F16, DETECT>), a.grid, dim3(kThreads), a.lds_reserve, a.stream,
-                       r, W, a.n, a.x_in, a.v_in, a.x_out, a.v_out, a.lr, a.mu, a.wd, a.c,
-                       a.found_inf);
+    for (uint32_t w = 0; w < XS_MAX_REPLICAS; ++w) r.p[w] = w < W ? l.replicas[w] : nullptr;
+    if (detect)
+        hipLaunchKernelGGL((reduce_sgd_anyw_kernel<GT, true>), l.grid, dim3(kThreads), l.lds_reserve,
+                           l.stream, r, W, l.a);
+    else
+        hipLaunchKernelGGL((reduce_sgd_anyw_kernel<GT, false>), l.grid, dim3(kThreads), l.lds_reserve,
+                           l.stream, r, W, l.a);
 }
 
 int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64_t n,
                       const float *x_in, const float *v_in, float *x_out, float *v_out,
                       const xs_sgd_hparams &hp, int32_t *found_inf, bool detect,
-                      hipStream_t stream)
+                      void *model_copy, int model_copy_dtype, hipStream_t stream)
 {
     const int cus = compute_units();
     if (cus < 0) return cus;
-    const bool f16 = dtype == XS_F16;
-    const uint64_t vec = f16 ? 8 : 4;
+    const bool half = dtype != XS_F32;
+    const uint64_t vec = half ? 8 : 4;
     uint64_t blocks = (n / vec + kThreads - 1) / kThreads;
     if (blocks == 0) blocks = 1;   // tail only
     if (g_tuning.reduce_wg_per_cu > 0) {
@@ -374,41 +252,39 @@ int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64
         blocks = (uint64_t)g_tuning.reduce_max_wg;
     if (blocks > 0x7fffffffull) blocks = 0x7fffffffull;   // the loop covers the rest
 
-    LaunchArgs a;
-    a.replicas = replicas;
-    a.n = n;
-    a.x_in = x_in; a.v_in = v_in; a.x_out = x_out; a.v_out = v_out;
-    a.lr = hp.lr; a.mu = hp.momentum; a.wd = hp.weight_decay;
+    Launch l;
+    l.replicas = replicas;
+    l.a.n = n;
+    l.a.x_in = x_in; l.a.v_in = v_in; l.a.x_out = x_out; l.a.v_out = v_out;
+    l.a.lr = hp.lr; l.a.mu = hp.momentum; l.a.wd = hp.weight_decay;
     // one constant for averaging and loss scale: inv_loss_scale * (1/W), rounded to fp32 twice
     volatile float one_over_w = 1.0f / (float)W;
-    a.c = hp.inv_loss_scale * one_over_w;
-    a.found_inf = found_inf;
-    a.grid = dim3((unsigned)blocks);
-    a.stream = stream;
+    l.a.c = hp.inv_loss_scale * one_over_w;
+    l.a.found_inf = found_inf;
+    l.a.model_copy = model_copy;
+    l.a.model_copy_dtype = model_copy_dtype;
+    l.grid = dim3((unsigned)blocks);
+    l.stream = stream;
     // Measured on MI355X: the pass is fastest with about 100-120 KB of loads in flight per
     // compute unit; more wavefronts than that only disorder the DRAM access stream.  The
     // LDS reservation (unused by the kernel) caps residency at 10 one-wave workgroups per
-    // compute unit for fp32 gradients (12 loads per lane) and 5 for fp16 (20 loads per lane).
-    // Every stream is touched once per lane -> all non-temporal (fp16 without the lane
-    // exchange: a lane's two state vectors share cache lines with its neighbours', so state
-    // loads stay cacheable there).
-    const int lds_auto = f16 ? 32768 : 16384;
-    a.lds_reserve = (unsigned)(g_tuning.reduce_lds_reserve < 0 ? lds_auto : g_tuning.reduce_lds_reserve);
-    a.shuffle = g_tuning.f16_state_shuffle != 0;
-    const int ntl = g_tuning.nt_loads < 0 ? 1 : g_tuning.nt_loads;
-    const int nts = g_tuning.nt_stores < 0 ? 1 : g_tuning.nt_stores;
-    const int ntx = g_tuning.nt_state_loads < 0 ? ((f16 && !a.shuffle) ? 0 : 1) : g_tuning.nt_state_loads;
-    const int nt = (ntl ? 1 : 0) | (nts ? 2 : 0) | (ntx ? 4 : 0);
+    // compute unit for fp32 gradients (12 loads per lane) and 5 for half-precision ones
+    // (20 loads per lane at W = 16).
+    const int lds_auto = half ? 32768 : 16384;
+    l.lds_reserve = (unsigned)(g_tuning.reduce_lds_reserve < 0 ? lds_auto : g_tuning.reduce_lds_reserve);
+    const bool ntg = g_tuning.nt_grads != 0, nts = g_tuning.nt_state != 0;
 
     switch (W) {
-    case 1: launch_w<1>(a, f16, detect, nt); break;
-    case 2: launch_w<2>(a, f16, detect, nt); break;
-    case 4: launch_w<4>(a, f16, detect, nt); break;
-    case 8: launch_w<8>(a, f16, detect, nt); break;
-    case 16: launch_w<16>(a, f16, detect, nt); break;
+    case 2: launch_w<2>(l, dtype, detect, ntg, nts); break;
+    case 4: launch_w<4>(l, dtype, detect, ntg, nts); break;
+    case 8: launch_w<8>(l, dtype, detect, ntg, nts); break;
+    case 16: launch_w<16>(l, dtype, detect, ntg, nts); break;
     default:
-        if (f16) { if (detect) launch_anyw<true, true>(a, W); else launch_anyw<true, false>(a, W); }
-        else     { if (detect) launch_anyw<false, true>(a, W); else launch_anyw<false, false>(a, W); }
+        switch (dtype) {
+        case XS_F16: launch_anyw<XS_F16>(l, W, detect); break;
+        case XS_BF16: launch_anyw<XS_BF16>(l, W, detect); break;
+        default: launch_anyw<XS_F32>(l, W, detect); break;
+        }
     }
     XS_HIP_TRY(hipGetLastError());
     return XS_OK;

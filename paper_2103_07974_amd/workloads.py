@@ -93,7 +93,7 @@ class Workload:
     name: str
     shapes: Tuple[Shape, ...]
     W: int                      # number of worker replicas resident on the GPU
-    grad_dtype: str             # "f32" or "f16"
+    grad_dtype: str             # "f32", "f16" or "bf16"
     grad_std: float
     param_std: float
     lr: float
@@ -121,7 +121,7 @@ class Workload:
 
     @property
     def torch_grad_dtype(self) -> torch.dtype:
-        return torch.float32 if self.grad_dtype == "f32" else torch.float16
+        return {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[self.grad_dtype]
 
 
 def _wl(name, shapes, **kw) -> Workload:
@@ -145,9 +145,10 @@ WORKLOADS = {w.name: w for w in
              (TINY_MLP, RESNET50, VGG16, BERT_LARGE_F16, BERT_LARGE_F16_INF)}
 
 
-def scaled(w: Workload, name: str, shapes: Sequence[Shape], W: int | None = None) -> Workload:
+def scaled(w: Workload, name: str, shapes: Sequence[Shape], W: int | None = None,
+           grad_dtype: str | None = None) -> Workload:
     """Same value recipe as `w` on another tensor list (reduced parity cases)."""
-    return _wl(name, shapes, W=w.W if W is None else W, grad_dtype=w.grad_dtype,
+    return _wl(name, shapes, W=w.W if W is None else W, grad_dtype=grad_dtype or w.grad_dtype,
                grad_std=w.grad_std, param_std=w.param_std, lr=w.lr, momentum=w.momentum,
                weight_decay=w.weight_decay, loss_scale=w.loss_scale,
                inf_fraction=w.inf_fraction, seed=w.seed)
@@ -172,8 +173,8 @@ def make_params(w: Workload, device="cpu") -> List[torch.Tensor]:
 def make_replica_grads(w: Workload, replica: int, device="cpu") -> List[torch.Tensor]:
     """Per-tensor gradients of worker `replica` ~ N(0, grad_std), seed = base+1+replica.
 
-    For fp16 workloads the values are the *scaled* gradients (already multiplied by
-    the loss scale is not modelled: the stated std applies to the stored values).
+    For half-precision workloads the stored values are the loss-scaled gradients; the
+    stated std applies to the stored values.
     With inf_fraction > 0, that share of replica 0's elements, at seeded distinct
     positions over the whole tensor list, is set to +inf.
     """

@@ -29,23 +29,24 @@ XS_F32 = 0
 XS_F16 = 1
 XS_MAX_REPLICAS = 32
 
+XS_BF16 = 2
+
 TUNE_REDUCE_WG_PER_CU = 0
 TUNE_COPY_WG_PER_CU = 1
-TUNE_NT_LOADS = 2
-TUNE_NT_STORES = 3
-TUNE_NT_STATE_LOADS = 4
-TUNE_REDUCE_LDS_RESERVE = 5
-TUNE_REDUCE_MAX_WG = 6
-TUNE_COPY_MAX_WG = 7
-TUNE_COPY_NT = 8
-TUNE_GATHER_LDS_RESERVE = 9
-TUNE_F16_STATE_SHUFFLE = 10
-N_TUNING_KEYS = 11
+TUNE_NT_GRADS = 2
+TUNE_NT_STATE = 3
+TUNE_REDUCE_LDS_RESERVE = 4
+TUNE_REDUCE_MAX_WG = 5
+TUNE_COPY_MAX_WG = 6
+TUNE_COPY_NT = 7
+TUNE_GATHER_LDS_RESERVE = 8
+N_TUNING_KEYS = 9
 
 EXPORTS = [
     "xs_status_string", "xs_last_error", "xs_bucket_layout", "xs_plan_create", "xs_plan_destroy",
     "xs_plan_bucket_elems", "xs_plan_n_tensors", "xs_fuse_pack", "xs_fuse_unpack",
-    "xs_fused_reduce_sgd", "xs_fused_gather_reduce_sgd", "xs_app_create", "xs_app_destroy", "xs_app_sync", "xs_crossover_step",
+    "xs_fused_reduce_sgd", "xs_fused_reduce_sgd_mp", "xs_fused_gather_reduce_sgd",
+    "xs_fused_gather_reduce_sgd_mp", "xs_app_create", "xs_app_destroy", "xs_app_sync", "xs_crossover_step",
     "xs_crossover_drain", "xs_app_wait_sync", "xs_tuning_set", "xs_tuning_get", "xs_standin_alu",
 ]
 
@@ -59,6 +60,11 @@ class XsError(RuntimeError):
 class SgdHparams(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_float), ("momentum", ctypes.c_float),
                 ("weight_decay", ctypes.c_float), ("inv_loss_scale", ctypes.c_float)]
+
+
+class MpOptions(ctypes.Structure):
+    _fields_ = [("model_copy", ctypes.c_void_p), ("model_copy_dtype", ctypes.c_int),
+                ("view_dtype", ctypes.c_int)]
 
 
 COMPUTE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
@@ -105,8 +111,15 @@ def lib() -> ctypes.CDLL:
     L.xs_fused_reduce_sgd.argtypes = [ctypes.POINTER(vp), ctypes.c_uint32, ctypes.c_int,
                                       ctypes.c_uint64, vp, vp, vp, vp,
                                       ctypes.POINTER(SgdHparams), vp, vp]
+    L.xs_fused_reduce_sgd_mp.argtypes = [ctypes.POINTER(vp), ctypes.c_uint32, ctypes.c_int,
+                                         ctypes.c_uint64, vp, vp, vp, vp,
+                                         ctypes.POINTER(SgdHparams), vp,
+                                         ctypes.POINTER(MpOptions), vp]
     L.xs_fused_gather_reduce_sgd.argtypes = [vp, vp, ctypes.c_uint32, vp, vp, vp, vp, vp,
                                              ctypes.POINTER(SgdHparams), vp, vp]
+    L.xs_fused_gather_reduce_sgd_mp.argtypes = [vp, vp, ctypes.c_uint32, vp, vp, vp, vp, vp,
+                                                ctypes.POINTER(SgdHparams), vp,
+                                                ctypes.POINTER(MpOptions), vp]
     L.xs_app_create.argtypes = [ctypes.POINTER(AppDesc), ctypes.POINTER(vp)]
     L.xs_app_destroy.argtypes = [vp]
     L.xs_app_sync.argtypes = [vp, vp]
@@ -157,7 +170,9 @@ def dtype_code(dtype: torch.dtype) -> int:
         return XS_F32
     if dtype == torch.float16:
         return XS_F16
-    raise TypeError(f"unsupported gradient dtype {dtype}")
+    if dtype == torch.bfloat16:
+        return XS_BF16
+    raise TypeError(f"unsupported element dtype {dtype}")
 
 
 # ---------------------------------------------------------------- layout / plan
@@ -229,16 +244,26 @@ def fused_reduce_sgd(replica_buckets: Sequence[torch.Tensor], n_elems: int, para
                      inv_loss_scale: float = 1.0, params_out: Optional[torch.Tensor] = None,
                      momentum_out: Optional[torch.Tensor] = None,
                      found_inf: Optional[torch.Tensor] = None, stream=None,
-                     grad_dtype: Optional[torch.dtype] = None) -> None:
+                     grad_dtype: Optional[torch.dtype] = None,
+                     model_copy: Optional[torch.Tensor] = None) -> None:
+    """model_copy: optional fp16/bf16 tensor (bucket layout) that receives the updated
+    parameters in the same pass (xs_fused_reduce_sgd_mp)."""
     W = len(replica_buckets)
     arr = (ctypes.c_void_p * max(W, 1))(*[_dptr(b) for b in replica_buckets])
     if grad_dtype is None:
         grad_dtype = replica_buckets[0].dtype if W else torch.float32
     hp = SgdHparams(lr, mu, wd, inv_loss_scale)
-    _check(lib().xs_fused_reduce_sgd(arr, W, dtype_code(grad_dtype), int(n_elems), _dptr(params),
-                                     _dptr(momentum), _dptr(params_out), _dptr(momentum_out),
-                                     ctypes.byref(hp), _dptr(found_inf), _stream_ptr(stream)),
-           "xs_fused_reduce_sgd")
+    if model_copy is None:
+        _check(lib().xs_fused_reduce_sgd(arr, W, dtype_code(grad_dtype), int(n_elems),
+                                         _dptr(params), _dptr(momentum), _dptr(params_out),
+                                         _dptr(momentum_out), ctypes.byref(hp), _dptr(found_inf),
+                                         _stream_ptr(stream)), "xs_fused_reduce_sgd")
+        return
+    mp = MpOptions(_dptr(model_copy), dtype_code(model_copy.dtype), XS_F32)
+    _check(lib().xs_fused_reduce_sgd_mp(arr, W, dtype_code(grad_dtype), int(n_elems), _dptr(params),
+                                        _dptr(momentum), _dptr(params_out), _dptr(momentum_out),
+                                        ctypes.byref(hp), _dptr(found_inf), ctypes.byref(mp),
+                                        _stream_ptr(stream)), "xs_fused_reduce_sgd_mp")
 
 
 def gather_pointer_table(grads: Sequence[Sequence[torch.Tensor]], device=None) -> torch.Tensor:
@@ -258,13 +283,24 @@ def fused_gather_reduce_sgd(plan: Plan, grad_ptrs: torch.Tensor, W: int, params:
                             params_out: Optional[torch.Tensor] = None,
                             momentum_out: Optional[torch.Tensor] = None,
                             param_tensor_ptrs: Optional[torch.Tensor] = None,
-                            found_inf: Optional[torch.Tensor] = None, stream=None) -> None:
+                            found_inf: Optional[torch.Tensor] = None, stream=None,
+                            view_dtype: torch.dtype = torch.float32) -> None:
+    """view_dtype: element type of the per-layer views behind param_tensor_ptrs (fp32, or
+    fp16/bf16 model weights written straight from the fp32 master update)."""
     hp = SgdHparams(lr, mu, wd, inv_loss_scale)
-    _check(lib().xs_fused_gather_reduce_sgd(plan.handle, _dptr(grad_ptrs), int(W), _dptr(params),
-                                            _dptr(momentum), _dptr(params_out), _dptr(momentum_out),
-                                            _dptr(param_tensor_ptrs), ctypes.byref(hp),
-                                            _dptr(found_inf), _stream_ptr(stream)),
-           "xs_fused_gather_reduce_sgd")
+    if view_dtype == torch.float32:
+        _check(lib().xs_fused_gather_reduce_sgd(plan.handle, _dptr(grad_ptrs), int(W),
+                                                _dptr(params), _dptr(momentum), _dptr(params_out),
+                                                _dptr(momentum_out), _dptr(param_tensor_ptrs),
+                                                ctypes.byref(hp), _dptr(found_inf),
+                                                _stream_ptr(stream)), "xs_fused_gather_reduce_sgd")
+        return
+    mp = MpOptions(None, XS_F16, dtype_code(view_dtype))
+    _check(lib().xs_fused_gather_reduce_sgd_mp(plan.handle, _dptr(grad_ptrs), int(W), _dptr(params),
+                                               _dptr(momentum), _dptr(params_out),
+                                               _dptr(momentum_out), _dptr(param_tensor_ptrs),
+                                               ctypes.byref(hp), _dptr(found_inf), ctypes.byref(mp),
+                                               _stream_ptr(stream)), "xs_fused_gather_reduce_sgd_mp")
 
 
 # ---------------------------------------------------------------- crossover

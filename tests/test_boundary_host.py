@@ -126,4 +126,30 @@ def test_tuning_roundtrip_and_range():
         xs.tuning_set(99, 1)
     assert xs.tuning_get(xs.TUNE_REDUCE_LDS_RESERVE) == -1      # per-dtype default
     with pytest.raises(xs.XsError):
-        xs.tuning_set(xs.TUNE_NT_LOADS, 2)
+        xs.tuning_set(xs.TUNE_NT_GRADS, 2)
+    with pytest.raises(xs.XsError):
+        xs.tuning_set(xs.N_TUNING_KEYS, 0)
+
+
+def test_header_tuning_enum_matches_binding():
+    text = open(HEADER).read()
+    for name, value in re.findall(r"XS_(TUNE_[A-Z_]+) = (\d+)", text):
+        if name == "TUNE_COUNT":
+            assert int(value) == xs.N_TUNING_KEYS
+        else:
+            assert getattr(xs, name) == int(value), name
+
+
+def test_mixed_precision_option_validation():
+    L = xs.lib()
+    arr = (ctypes.c_void_p * 2)(FAKE + 0x20000, FAKE + 0x30000)
+    h = xs.SgdHparams(0.1, 0.9, 0.0, 1.0)
+
+    def reduce_mp(copy, dt):
+        mp = xs.MpOptions(copy, dt, 0)
+        return L.xs_fused_reduce_sgd_mp(arr, 2, xs.XS_F32, 16, FAKE, FAKE + 0x1000, None, None,
+                                        ctypes.byref(h), None, ctypes.byref(mp), None)
+    assert reduce_mp(FAKE + 0x5000, xs.XS_F32) == xs.XS_ERR_UNSUPPORTED      # not a half type
+    assert reduce_mp(FAKE + 0x5002, xs.XS_F16) == xs.XS_ERR_ALIGNMENT
+    assert reduce_mp(FAKE + 0x1000, xs.XS_BF16) == xs.XS_ERR_INVALID_ARG     # on top of momentum
+    assert reduce_mp(FAKE + 0x20010, xs.XS_F16) == xs.XS_ERR_INVALID_ARG     # on top of a replica

@@ -106,16 +106,15 @@ def test_any_W(W, dtype):
             assert _ulp_distance(gx, x32) == 0 and _ulp_distance(gv, v32) == 0
 
 
-@pytest.mark.parametrize("wg_per_cu,lds", [(0, 8192), (0, 0), (1, 0), (8, 8192), (32, 16384)])
-@pytest.mark.parametrize("nt_loads,nt_stores,nt_state", [(0, 0, 0), (1, 0, 0), (1, 1, 1), (0, 1, 1)])
-def test_launch_shapes_give_identical_results(wg_per_cu, lds, nt_loads, nt_stores, nt_state):
+@pytest.mark.parametrize("wg_per_cu,lds", [(0, -1), (0, 0), (1, 0), (8, 8192), (32, 16384)])
+@pytest.mark.parametrize("nt_grads,nt_state", [(0, 0), (1, 0), (1, 1), (0, 1)])
+def test_launch_shapes_give_identical_results(wg_per_cu, lds, nt_grads, nt_state):
     old = [xs.tuning_get(k) for k in range(xs.N_TUNING_KEYS)]
     try:
         xs.tuning_set(xs.TUNE_REDUCE_WG_PER_CU, wg_per_cu)
         xs.tuning_set(xs.TUNE_REDUCE_LDS_RESERVE, lds)
-        xs.tuning_set(xs.TUNE_NT_LOADS, nt_loads)
-        xs.tuning_set(xs.TUNE_NT_STORES, nt_stores)
-        xs.tuning_set(xs.TUNE_NT_STATE_LOADS, nt_state)
+        xs.tuning_set(xs.TUNE_NT_GRADS, nt_grads)
+        xs.tuning_set(xs.TUNE_NT_STATE, nt_state)
         n = 3 * 1024 * 1024 + 1
         for dtype in (torch.float32, torch.float16):
             reps, x, v = _make(n, 8, dtype, seed=3000)
