@@ -265,12 +265,12 @@ int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64
     l.a.model_copy_dtype = model_copy_dtype;
     l.grid = dim3((unsigned)blocks);
     l.stream = stream;
-    // Measured on MI355X: the pass is fastest with about 100-120 KB of loads in flight per
-    // compute unit; more wavefronts than that only disorder the DRAM access stream.  The
-    // LDS reservation (unused by the kernel) caps residency at 10 one-wave workgroups per
-    // compute unit for fp32 gradients (12 loads per lane) and 5 for half-precision ones
-    // (20 loads per lane at W = 16).
-    const int lds_auto = half ? 32768 : 16384;
+    // Measured on MI355X: the pass is fastest with 10 one-wave workgroups per compute unit
+    // (fp32 W = 8: 12 loads per lane, about 120 KB in flight per compute unit; fp16 W = 16:
+    // 20 loads per lane); more wavefronts than that only disorder the DRAM access stream,
+    // fewer expose the latency of the kernel's prologue.  The LDS reservation (unused by the
+    // kernel) is what caps the residency.
+    const int lds_auto = 16384;
     l.lds_reserve = (unsigned)(g_tuning.reduce_lds_reserve < 0 ? lds_auto : g_tuning.reduce_lds_reserve);
     const bool ntg = g_tuning.nt_grads != 0, nts = g_tuning.nt_state != 0;
 
