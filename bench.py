@@ -1,9 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the fused gradient-synchronisation path on one MI355X.
 
-A step is one whole synchronisation of the ResNet-50-shaped gradient set: W = 8 packs,
-the fused reduce + SGD, and the unpack of the parameters, on one stream, inputs resident
-in HBM.  `value` is (W*s + 16) * N bytes (W replica buckets, parameters and momentum read,
+A step is one whole synchronisation of the ResNet-50-shaped gradient set: the W = 8 packs
+(one launch), the fused reduce + SGD, and the unpack of the parameters, on one stream, inputs
+resident in HBM.  `value` is (W*s + 16) * N bytes (W replica buckets, parameters and momentum read,
 parameters and momentum written) divided by the time of the whole step.  `roofline`
 covers the fused reduce + SGD kernel alone, timed with events inside the timed region.
 The VGG-16- and BERT-large-shaped sets, the tiny set's latency and the two-stream
@@ -43,8 +43,7 @@ def time_steps(tasks, steps, warmup, stream):
 
     def one(task, pair=None):
         w = task.workload
-        for r in range(w.W):
-            xs.fuse_pack(task.gplan, task.grad_tables[r], task.buckets[r], None, stream)
+        xs.fuse_pack_many(task.gplan, task.grad_tables, task.buckets, None, stream)
         if pair:
             pair[0].record(stream)
         xs.fused_reduce_sgd(task.buckets, task.n_bucket, task.params, task.momentum,
@@ -86,6 +85,9 @@ def time_kernels(task, stream, reps=30, warm=5):
 
     out["pack_ms"] = _median(run(lambda i: xs.fuse_pack(
         task.gplan, task.grad_tables[i % w.W], task.buckets[i % w.W], None, stream)))
+    out["pack_all_replicas_ms"] = _median(run(lambda i: xs.fuse_pack_many(
+        task.gplan, task.grad_tables, task.buckets, None, stream)))
+    out["pack_all_replicas_GBs"] = w.W * task.pack_bytes() / out["pack_all_replicas_ms"] / 1e6
     red = run(lambda i: xs.fused_reduce_sgd(
         task.buckets, task.n_bucket, task.params, task.momentum, w.lr, w.momentum,
         w.weight_decay, 1.0 / w.loss_scale, stream=stream))

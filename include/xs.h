@@ -103,6 +103,12 @@ uint32_t xs_plan_n_tensors(const xs_plan *plan);
 int xs_fuse_pack(const xs_plan *plan, const void *const *tensor_ptrs, void *bucket,
                  int32_t *found_inf, void *hip_stream);
 
+/* The same for n (pointer table, bucket) pairs of one plan in a single launch - the W workers'
+ * packs of one synchronisation.  tensor_ptr_tables and buckets are host arrays of n device
+ * pointers; n <= XS_MAX_REPLICAS; n == 0 is a no-op. */
+int xs_fuse_pack_many(const xs_plan *plan, const void *const *const *tensor_ptr_tables,
+                      void *const *buckets, uint32_t n, int32_t *found_inf, void *hip_stream);
+
 /* Unpack: inverse of pack.  Copies each tensor's range of the bucket to
  * tensor_ptrs[t]; padding is ignored.  Same pointer conventions as pack. */
 int xs_fuse_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,

@@ -253,7 +253,32 @@ extern "C" int xs_fuse_pack(const xs_plan *plan, const void *const *tensor_ptrs,
     if (!aligned16(bucket)) return fail(XS_ERR_ALIGNMENT, "xs_fuse_pack: bucket is not 16-byte aligned");
     if (found_inf && ((uintptr_t)found_inf & 3u))
         return fail(XS_ERR_ALIGNMENT, "xs_fuse_pack: found_inf is not 4-byte aligned");
-    return launch_pack(plan, tensor_ptrs, bucket, found_inf, (hipStream_t)hip_stream);
+    const void *table = tensor_ptrs;
+    return launch_pack(plan, &table, &bucket, 1, found_inf, (hipStream_t)hip_stream);
+}
+
+// The W workers' packs of one synchronisation in a single launch.
+extern "C" int xs_fuse_pack_many(const xs_plan *plan, const void *const *const *tensor_ptr_tables,
+                                 void *const *buckets, uint32_t n, int32_t *found_inf,
+                                 void *hip_stream)
+{
+    if (!plan || plan->magic != XS_PLAN_MAGIC)
+        return fail(XS_ERR_INVALID_ARG, "xs_fuse_pack_many: plan is NULL or not a plan");
+    if (n > XS_MAX_REPLICAS)
+        return fail(XS_ERR_INVALID_ARG, "xs_fuse_pack_many: n = %u exceeds %d", n, XS_MAX_REPLICAS);
+    if (n == 0 || plan->n_chunks == 0) return XS_OK;
+    if (!tensor_ptr_tables || !buckets)
+        return fail(XS_ERR_INVALID_ARG, "xs_fuse_pack_many: tensor_ptr_tables/buckets is NULL");
+    if (found_inf && ((uintptr_t)found_inf & 3u))
+        return fail(XS_ERR_ALIGNMENT, "xs_fuse_pack_many: found_inf is not 4-byte aligned");
+    for (uint32_t i = 0; i < n; ++i) {
+        if (!tensor_ptr_tables[i] || !buckets[i])
+            return fail(XS_ERR_INVALID_ARG, "xs_fuse_pack_many: entry %u is NULL", i);
+        if (!aligned16(buckets[i]))
+            return fail(XS_ERR_ALIGNMENT, "xs_fuse_pack_many: buckets[%u] is not 16-byte aligned", i);
+    }
+    return launch_pack(plan, (const void *const *)tensor_ptr_tables, buckets, n, found_inf,
+                       (hipStream_t)hip_stream);
 }
 
 extern "C" int xs_fuse_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,

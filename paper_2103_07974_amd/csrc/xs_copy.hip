@@ -87,10 +87,17 @@ struct Elem<2> { typedef uint16_t type; };
 // UNPACK = false: tensors -> bucket (padding zero-filled, optional overflow flag)
 // UNPACK = true : bucket -> tensors (padding skipped)
 // DT: element type of the plan (XS_F32 / XS_F16 / XS_BF16); it matters only for the overflow test.
+// One launch can serve several (pointer table, bucket) pairs of the same plan - the W
+// workers' packs of one synchronisation: work item = (pair, chunk), pair-major.
+struct CopyPairs {
+    const uintptr_t *tables[XS_MAX_REPLICAS];
+    unsigned char *buckets[XS_MAX_REPLICAS];
+};
+
 template <bool UNPACK, bool DETECT, int DT, bool LDS_TABLE, bool NT>
 __global__ __launch_bounds__(kCopyThreads) void copy_kernel(
-    PlanTables tb, uint32_t n_tensors, uint32_t n_chunks, const uintptr_t *tensor_ptrs,
-    unsigned char *bucket, int32_t *found_inf)
+    PlanTables tb, uint32_t n_tensors, uint32_t n_chunks, uint32_t n_pairs, CopyPairs pairs,
+    int32_t *found_inf)
 {
     constexpr int ES = Grad<DT>::ES;
     typedef typename Elem<ES>::type elem_t;
@@ -102,7 +109,12 @@ __global__ __launch_bounds__(kCopyThreads) void copy_kernel(
     }
     bool bad = false;
 
-    for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    const uint64_t n_items = (uint64_t)n_pairs * n_chunks;
+    for (uint64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const uint32_t pair = (uint32_t)(item / n_chunks);
+        const uint32_t c = (uint32_t)(item - (uint64_t)pair * n_chunks);
+        const uintptr_t *tensor_ptrs = pairs.tables[pair];
+        unsigned char *bucket = pairs.buckets[pair];
         uint32_t t, first_chunk;
         if constexpr (LDS_TABLE) {
             t = find_tensor(s_prefix, n_tensors + 1, c);
@@ -176,23 +188,28 @@ __global__ __launch_bounds__(kCopyThreads) void copy_kernel(
 }
 
 template <bool UNPACK, bool DETECT, int DT>
-static int launch_copy(const xs_plan *plan, const void *tensor_ptrs, void *bucket,
-                       int32_t *found_inf, hipStream_t stream)
+static int launch_copy(const xs_plan *plan, const void *const *tables, void *const *buckets,
+                       uint32_t n_pairs, int32_t *found_inf, hipStream_t stream)
 {
     const int cus = compute_units();
     if (cus < 0) return cus;
-    uint32_t blocks = (uint32_t)cus * (uint32_t)g_tuning.copy_wg_per_cu;
-    if (g_tuning.copy_max_wg > 0 && blocks > (uint32_t)g_tuning.copy_max_wg)
-        blocks = (uint32_t)g_tuning.copy_max_wg;
-    if (blocks > plan->n_chunks) blocks = plan->n_chunks;
+    CopyPairs pairs;
+    for (uint32_t i = 0; i < XS_MAX_REPLICAS; ++i) {
+        pairs.tables[i] = i < n_pairs ? (const uintptr_t *)tables[i] : nullptr;
+        pairs.buckets[i] = i < n_pairs ? (unsigned char *)buckets[i] : nullptr;
+    }
+    const uint64_t n_items = (uint64_t)n_pairs * plan->n_chunks;
+    uint64_t blocks = (uint64_t)cus * (uint64_t)g_tuning.copy_wg_per_cu;
+    if (g_tuning.copy_max_wg > 0 && blocks > (uint64_t)g_tuning.copy_max_wg)
+        blocks = (uint64_t)g_tuning.copy_max_wg;
+    if (blocks > n_items) blocks = n_items;
     const bool lds = plan->n_tensors + 1 <= kLdsPrefixCap;
     const size_t lds_bytes = lds ? (size_t)(plan->n_tensors + 1) * 4 : 0;
     const bool nt = g_tuning.copy_nt != 0;
-    const dim3 grid(blocks), block(kCopyThreads);
+    const dim3 grid((unsigned)blocks), block(kCopyThreads);
 #define XS_COPY_LAUNCH(LDS, NT)                                                                   \
     hipLaunchKernelGGL((copy_kernel<UNPACK, DETECT, DT, LDS, NT>), grid, block, (LDS) ? lds_bytes : 0, \
-                       stream, plan->tables, plan->n_tensors, plan->n_chunks,                     \
-                       (const uintptr_t *)tensor_ptrs, (unsigned char *)bucket, found_inf)
+                       stream, plan->tables, plan->n_tensors, plan->n_chunks, n_pairs, pairs, found_inf)
     if (lds) { if (nt) XS_COPY_LAUNCH(true, true); else XS_COPY_LAUNCH(true, false); }
     else     { if (nt) XS_COPY_LAUNCH(false, true); else XS_COPY_LAUNCH(false, false); }
 #undef XS_COPY_LAUNCH
@@ -200,26 +217,28 @@ static int launch_copy(const xs_plan *plan, const void *tensor_ptrs, void *bucke
     return XS_OK;
 }
 
-int launch_pack(const xs_plan *plan, const void *const *tensor_ptrs, void *bucket,
-                int32_t *found_inf, hipStream_t stream)
+int launch_pack(const xs_plan *plan, const void *const *tables, void *const *buckets,
+                uint32_t n_pairs, int32_t *found_inf, hipStream_t stream)
 {
     if (!found_inf)   // a plain copy: only the element size matters
         return plan->elem_size == 4
-                   ? launch_copy<false, false, XS_F32>(plan, tensor_ptrs, bucket, nullptr, stream)
-                   : launch_copy<false, false, XS_F16>(plan, tensor_ptrs, bucket, nullptr, stream);
+                   ? launch_copy<false, false, XS_F32>(plan, tables, buckets, n_pairs, nullptr, stream)
+                   : launch_copy<false, false, XS_F16>(plan, tables, buckets, n_pairs, nullptr, stream);
     switch (plan->dtype) {
-    case XS_F16: return launch_copy<false, true, XS_F16>(plan, tensor_ptrs, bucket, found_inf, stream);
-    case XS_BF16: return launch_copy<false, true, XS_BF16>(plan, tensor_ptrs, bucket, found_inf, stream);
-    default: return launch_copy<false, true, XS_F32>(plan, tensor_ptrs, bucket, found_inf, stream);
+    case XS_F16: return launch_copy<false, true, XS_F16>(plan, tables, buckets, n_pairs, found_inf, stream);
+    case XS_BF16: return launch_copy<false, true, XS_BF16>(plan, tables, buckets, n_pairs, found_inf, stream);
+    default: return launch_copy<false, true, XS_F32>(plan, tables, buckets, n_pairs, found_inf, stream);
     }
 }
 
 int launch_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,
                   hipStream_t stream)
 {
+    const void *table = tensor_ptrs;
+    void *b = const_cast<void *>(bucket);
     if (plan->elem_size == 4)
-        return launch_copy<true, false, XS_F32>(plan, tensor_ptrs, const_cast<void *>(bucket), nullptr, stream);
-    return launch_copy<true, false, XS_F16>(plan, tensor_ptrs, const_cast<void *>(bucket), nullptr, stream);
+        return launch_copy<true, false, XS_F32>(plan, &table, &b, 1, nullptr, stream);
+    return launch_copy<true, false, XS_F16>(plan, &table, &b, 1, nullptr, stream);
 }
 
 }  // namespace xs

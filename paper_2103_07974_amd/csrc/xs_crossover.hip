@@ -1,7 +1,7 @@
 // Two-stream crossover driver (arXiv 2103.07974, Algorithm 1 and Section 2.1).
 //
 // A task's gradient computation runs on the compute stream; its synchronisation
-// (W packs, fused reduce + SGD, unpack; or the single gathering kernel when the task
+// (the W packs in one launch, fused reduce + SGD, unpack; or the single gathering kernel when the task
 // was created with XS_APP_FUSED_GATHER) runs on the sync stream.  Two events per
 // task carry the only dependencies the algorithm has:
 //   grads_ready  recorded on the compute stream after the task's computation;
@@ -133,11 +133,10 @@ static int enqueue_sync(xs_app *a, hipStream_t s)
     if (a->flags & XS_APP_FUSED_GATHER)
         return xs_fused_gather_reduce_sgd(a->gplan, a->gather_table, a->W, a->params, a->momentum,
                                           nullptr, nullptr, a->param_table, &a->hp, a->found_inf, s);
-    for (uint32_t w = 0; w < a->W; ++w) {
-        int rc = xs_fuse_pack(a->gplan, a->grad_tables[w], a->buckets[w], a->found_inf, s);
-        if (rc != XS_OK) return rc;
-    }
-    int rc = xs_fused_reduce_sgd((const void *const *)a->buckets.data(), a->W, a->gplan->dtype,
+    int rc = xs_fuse_pack_many(a->gplan, a->grad_tables.data(), a->buckets.data(), a->W,
+                               a->found_inf, s);
+    if (rc != XS_OK) return rc;
+    rc = xs_fused_reduce_sgd((const void *const *)a->buckets.data(), a->W, a->gplan->dtype,
                                  a->gplan->bucket_elems, a->params, a->momentum, nullptr, nullptr,
                                  &a->hp, a->found_inf, s);
     if (rc != XS_OK) return rc;

@@ -76,8 +76,9 @@ constexpr uint32_t XS_APP_MAGIC = 0x78734131u;   // "xsA1"
 
 namespace xs {
 // launchers implemented next to their kernels
-int launch_pack(const xs_plan *plan, const void *const *tensor_ptrs, void *bucket,
-                int32_t *found_inf, hipStream_t stream);
+int launch_pack(const xs_plan *plan, const void *const *tables /* host array of device tables */,
+                void *const *buckets /* host array */, uint32_t n_pairs, int32_t *found_inf,
+                hipStream_t stream);
 int launch_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,
                   hipStream_t stream);
 int launch_gather_reduce_sgd(const xs_plan *plan, const void *const *grad_ptrs, uint32_t W,

@@ -44,7 +44,8 @@ N_TUNING_KEYS = 9
 
 EXPORTS = [
     "xs_status_string", "xs_last_error", "xs_bucket_layout", "xs_plan_create", "xs_plan_destroy",
-    "xs_plan_bucket_elems", "xs_plan_n_tensors", "xs_fuse_pack", "xs_fuse_unpack",
+    "xs_plan_bucket_elems", "xs_plan_n_tensors", "xs_fuse_pack", "xs_fuse_pack_many",
+    "xs_fuse_unpack",
     "xs_fused_reduce_sgd", "xs_fused_reduce_sgd_mp", "xs_fused_gather_reduce_sgd",
     "xs_fused_gather_reduce_sgd_mp", "xs_app_create", "xs_app_destroy", "xs_app_sync", "xs_crossover_step",
     "xs_crossover_drain", "xs_app_wait_sync", "xs_tuning_set", "xs_tuning_get", "xs_standin_alu",
@@ -107,6 +108,7 @@ def lib() -> ctypes.CDLL:
     L.xs_plan_bucket_elems.argtypes = [vp]; L.xs_plan_bucket_elems.restype = ctypes.c_uint64
     L.xs_plan_n_tensors.argtypes = [vp]; L.xs_plan_n_tensors.restype = ctypes.c_uint32
     L.xs_fuse_pack.argtypes = [vp, vp, vp, vp, vp]
+    L.xs_fuse_pack_many.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_uint32, vp, vp]
     L.xs_fuse_unpack.argtypes = [vp, vp, vp, vp]
     L.xs_fused_reduce_sgd.argtypes = [ctypes.POINTER(vp), ctypes.c_uint32, ctypes.c_int,
                                       ctypes.c_uint64, vp, vp, vp, vp,
@@ -232,6 +234,17 @@ def fuse_pack(plan: Plan, tensor_ptrs: torch.Tensor, bucket: torch.Tensor,
               found_inf: Optional[torch.Tensor] = None, stream=None) -> None:
     _check(lib().xs_fuse_pack(plan.handle, _dptr(tensor_ptrs), _dptr(bucket), _dptr(found_inf),
                               _stream_ptr(stream)), "xs_fuse_pack")
+
+
+def fuse_pack_many(plan: Plan, tensor_ptr_tables: Sequence[torch.Tensor],
+                   buckets: Sequence[torch.Tensor], found_inf: Optional[torch.Tensor] = None,
+                   stream=None) -> None:
+    """All workers' packs of one synchronisation in a single launch."""
+    n = len(buckets)
+    tabs = (ctypes.c_void_p * max(n, 1))(*[_dptr(t) for t in tensor_ptr_tables])
+    bks = (ctypes.c_void_p * max(n, 1))(*[_dptr(b) for b in buckets])
+    _check(lib().xs_fuse_pack_many(plan.handle, tabs, bks, n, _dptr(found_inf), _stream_ptr(stream)),
+           "xs_fuse_pack_many")
 
 
 def fuse_unpack(plan: Plan, bucket: torch.Tensor, tensor_ptrs: torch.Tensor, stream=None) -> None:

@@ -157,3 +157,36 @@ def test_pack_raises_the_overflow_flag(torch_dtype, np_dtype):
     torch.cuda.synchronize()
     assert int(flag.item()) == 1
     plan.destroy()
+
+
+@pytest.mark.parametrize("torch_dtype,np_dtype", [(torch.float32, np.float32), (torch.float16, np.float16)])
+def test_pack_many_equals_single_packs(torch_dtype, np_dtype):
+    """All workers' packs in one launch: every bucket bit-identical to the oracle's pack of that
+    worker's tensors, and the overflow flag raised if any worker's tensors hold a non-finite."""
+    rng = np.random.default_rng(23)
+    numel = [0, 5, 4097, 64, 20001, 3]
+    W = 5
+    offs = xs.bucket_layout(numel, 4)
+    plan = xs.Plan(numel, offs, torch_dtype)
+    hosts = [[_random_bits(rng, n, np_dtype) for n in numel] for _ in range(W)]
+    for h in hosts:                      # finite everywhere, for the flag check
+        for a in h:
+            bits = _bits(a)
+            mask = np.uint32(0x7f800000) if a.dtype.itemsize == 4 else np.uint16(0x7c00)
+            bits[(bits & mask) == mask] = 0
+    devs = [_device_tensors(h, torch_dtype, 1) for h in hosts]
+    tables = [xs.pointer_table(v) for _, v in devs]
+    buckets = [torch.full((offs[-1],), 3.0, dtype=torch_dtype, device="cuda") for _ in range(W)]
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    xs.fuse_pack_many(plan, tables, buckets, flag)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0
+    for h, b in zip(hosts, buckets):
+        want = oracle.pack(h, np.asarray(offs, dtype=np.uint64))
+        assert np.array_equal(_bits(b.cpu().numpy()), _bits(want))
+    devs[3][1][4][20000] = float("inf")           # worker 3, last element of the large tensor
+    xs.fuse_pack_many(plan, tables, buckets, flag)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 1
+    xs.fuse_pack_many(plan, [], [])               # n = 0 is a no-op
+    plan.destroy()
