@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the fused reduce + SGD kernel on the headline workload, from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a plain copy's reading of the same
 # counters (profiles/hbm_traffic_pmc_reduce_sgd_pack_unpack.md)
-MEASURED_TRAFFIC_BYTES = 1226779955
+MEASURED_TRAFFIC_BYTES = 1226785792
 
 
 def _median(xs_):
@@ -131,9 +131,9 @@ def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False,
     """Two tasks alternate as in Algorithm 1: one computes (a stand-in for forward + backward)
     while the other synchronises on the second stream.
 
-    standin="gemm": the configured chain of bf16 GEMMs.  standin="alu": a chain of elementwise
-    lgamma passes over 16M fp32 values - arithmetic-bound kernels of ordinary occupancy, the
-    kind of kernel a synchronisation wave can share a compute unit with."""
+    standin="gemm": the configured chain of bf16 GEMMs.  standin="alu": one arithmetic-only
+    kernel of ordinary occupancy and no memory traffic (xs_standin_alu) of the same duration -
+    the kind of kernel a synchronisation wave can share a compute unit with."""
     import torch
     from paper_2103_07974_amd import xs
     g = torch.Generator(device="cuda"); g.manual_seed(task_a.workload.seed + 100)
@@ -299,10 +299,14 @@ def traffic_probe():
             xs.fused_reduce_sgd(task.buckets, task.n_bucket, task.params, task.momentum,
                                 w.lr, w.momentum, w.weight_decay, 1.0)
             xs.fuse_unpack(task.pplan, task.params, task.param_table)
+            xs.fused_gather_reduce_sgd(task.gplan, task.gather_table, w.W, task.params,
+                                       task.momentum, w.lr, w.momentum, w.weight_decay, 1.0,
+                                       param_tensor_ptrs=task.param_table)
         torch.cuda.synchronize()
         print(json.dumps({"workload": w.name, "copy_bytes_each_way": n * 4,
                           "reduce_bytes": task.reduce_bytes(), "pack_bytes": task.pack_bytes(),
-                          "unpack_bytes": task.unpack_bytes(), "bucket_elems": task.n_bucket}))
+                          "unpack_bytes": task.unpack_bytes(), "gather_bytes": task.gather_bytes(True),
+                          "bucket_elems": task.n_bucket}))
         del task
     return 0
 
