@@ -79,7 +79,8 @@ int xs_bucket_layout(const uint64_t *numel, uint32_t n_tensors, uint64_t align_e
  * offsets[0] == 0, offsets[t]+numel[t] <= offsets[t+1], and offsets[n_tensors]
  * is the bucket length.  Elements between a tensor's end and the next offset
  * are padding.  dtype is the element type moved by pack/unpack with this plan.
- * xs_plan_create allocates small device tables and synchronises once.
+ * xs_plan_create allocates small device tables and synchronises once.  A plan must outlive
+ * every kernel that was enqueued with it (destroy it after the stream has drained).
  * n_tensors == 0 and numel[t] == 0 are valid.
  */
 typedef struct xs_plan xs_plan;
@@ -118,7 +119,7 @@ int xs_fuse_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_
  * Fused reduce + average + momentum-SGD (Algorithm 1, "Receive averaged
  * gradients" and "Model Update"), one pass over memory.  For every j < n_elems
  *     s = g_0[j] + g_1[j] + ... + g_{W-1}[j]     (left to right, fp32;
- *                                                 fp16 gradients widened first)
+ *                                                 fp16 / bf16 gradients widened first)
  *     g = s * (inv_loss_scale * (1/W))
  *     d = g + weight_decay * x[j];  v[j] = momentum * v[j] + d;  x[j] -= lr * v[j]
  * every operation rounded to fp32 separately (no fused multiply-add).
