@@ -114,3 +114,45 @@ def test_crossover_equals_standalone_training_bit_for_bit(N):
             assert np.array_equal(x, y)
     for x, y in zip(a["v"], b["v"]):
         assert np.array_equal(x, y)
+
+
+def test_equivalence_check_is_sensitive_to_a_missing_wait():
+    """A schedule that lets a task compute before its previous update has landed (what a
+    missing event wait would do) must end somewhere else than stand-alone training."""
+    T, W = 3, 2
+    shapes = [[6, 2], [9]]
+    rng = np.random.default_rng(33)
+    init = [[rng.standard_normal(n).astype(np.float32) for n in s] for s in shapes]
+
+    def run(broken):
+        p = [[a.copy() for a in task] for task in init]
+        v = [np.zeros(sum(s), np.float32) for s in shapes]
+        pending = {}
+
+        def grads(i, t):
+            return [[np.sin(q * (w + 1) + t).astype(np.float32) for q in p[i]] for w in range(W)]
+
+        def apply(i, g):
+            p[i], _ = oracle.sync_step(g, p[i], v[i], 0.1, 0.9, 1e-3, precision="f32")
+
+        for t in range(1, T + 1):
+            for i in range(2):
+                if not broken and i in pending:       # the wait: update before computing again
+                    apply(i, pending.pop(i))
+                g = grads(i, t)
+                if broken and i in pending:           # update lands after the computation started
+                    apply(i, pending.pop(i))
+                pending[i] = g
+        for i in sorted(pending):
+            apply(i, pending[i])
+        return p
+
+    good, bad = run(False), run(True)
+    ref = [[a.copy() for a in task] for task in init]
+    vref = [np.zeros(sum(s), np.float32) for s in shapes]
+    for i in range(2):
+        for t in range(1, T + 1):
+            g = [[np.sin(q * (w + 1) + t).astype(np.float32) for q in ref[i]] for w in range(W)]
+            ref[i], _ = oracle.sync_step(g, ref[i], vref[i], 0.1, 0.9, 1e-3, precision="f32")
+    assert all(np.array_equal(a, b) for ta, tb in zip(good, ref) for a, b in zip(ta, tb))
+    assert any(not np.array_equal(a, b) for ta, tb in zip(bad, ref) for a, b in zip(ta, tb))
