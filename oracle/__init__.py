@@ -195,6 +195,31 @@ def reduce_sgd_f32(replicas: Sequence[np.ndarray], x: np.ndarray, v: np.ndarray,
         raise ValueError("W must be >= 1")
 
 
+def reduce_sgd_per_tensor(replicas: Sequence[np.ndarray], x: np.ndarray, v: np.ndarray,
+                          offsets: np.ndarray, tensor_hp: Sequence[Sequence[float]],
+                          inv_loss_scale: float = 1.0) -> None:
+    """Average + update with hyper-parameters per tensor ("Model Update" of Algorithm 1 applied
+    with one (lr, mu, wd) triple per layer, the usual parameter groups of SGD: no weight decay
+    on biases and normalisation layers, per-group learning rates).
+
+    tensor_hp[t] = (lr, mu, wd) governs bucket elements offsets[t] .. offsets[t+1]-1, i.e.
+    tensor t and the padding behind it.  Working precision follows x (float64 or float32).
+    """
+    offsets = _u64(offsets)
+    if len(tensor_hp) + 1 != len(offsets):
+        raise ValueError("one hyper-parameter triple per tensor")
+    if x.dtype == np.float64:
+        step = reduce_sgd_f64
+    elif x.dtype == np.float32:
+        step = reduce_sgd_f32
+    else:
+        raise TypeError("x must be float64 or float32")
+    for t, (lr, mu, wd) in enumerate(tensor_hp):
+        a, b = int(offsets[t]), int(offsets[t + 1])
+        if b > a:
+            step([r[a:b] for r in replicas], x[a:b], v[a:b], lr, mu, wd, inv_loss_scale)
+
+
 def round_params(x: np.ndarray, dtype_code: int) -> np.ndarray:
     """float32 values rounded to binary16 / bfloat16 (ties to even); returns uint16 bit patterns."""
     _check_c(x, "x")
@@ -209,14 +234,16 @@ def round_params(x: np.ndarray, dtype_code: int) -> np.ndarray:
 
 def sync_step(grads: Sequence[Sequence[np.ndarray]], params: Sequence[np.ndarray],
               v_bucket: np.ndarray, lr: float, mu: float, wd: float,
-              inv_loss_scale: float = 1.0, align: int = 1, precision: str = "f64"):
+              inv_loss_scale: float = 1.0, align: int = 1, precision: str = "f64",
+              tensor_hp: Sequence[Sequence[float]] | None = None):
     """One whole synchronisation of one task: pack every worker's tensor list, test
     for overflow, average + update, unpack the new parameters.
 
     grads[w][t]: worker w's gradient tensor t (flat).  params[t]: float32 parameters.
     v_bucket: momentum in bucket layout (float64 for "f64", float32 for "f32"),
     updated in place.  Returns (new_params list in the working precision, found_inf).
-    A skipped step returns the parameters unchanged.
+    A skipped step returns the parameters unchanged.  tensor_hp, if given, replaces
+    (lr, mu, wd) by one triple per tensor.
     """
     numel = [p.size for p in params]
     offs = layout(numel, align)
@@ -225,7 +252,9 @@ def sync_step(grads: Sequence[Sequence[np.ndarray]], params: Sequence[np.ndarray
     x = pack([np.ascontiguousarray(p, dtype=np.float32) for p in params], offs).astype(work)
     if any_nonfinite(buckets, numel, offs):
         return unpack(x, numel, offs), True
-    if precision == "f64":
+    if tensor_hp is not None:
+        reduce_sgd_per_tensor(buckets, x, v_bucket, offs, tensor_hp, inv_loss_scale)
+    elif precision == "f64":
         reduce_sgd_f64(buckets, x, v_bucket, lr, mu, wd, inv_loss_scale)
     else:
         reduce_sgd_f32(buckets, x, v_bucket, lr, mu, wd, inv_loss_scale)
