@@ -207,6 +207,42 @@ int xs_fused_gather_reduce_sgd_mp(const xs_plan *gradient_plan, const void *cons
                                   int32_t *found_inf, const xs_mp_options *mp, void *hip_stream);
 
 /* ------------------------------------------------------------------------
+ * Hyper-parameters per tensor (beyond the paper, whose "Model Update" is a bare SGD(x, g):
+ * optimizers apply it with parameter groups - no weight decay on biases and normalisation
+ * layers, a learning rate per group).  One 16-byte record per tensor of the plan, in a device
+ * array the caller owns.  Record t governs bucket elements offsets[t] .. offsets[t+1]-1, i.e.
+ * tensor t and the padding behind it; the arithmetic per element is that of
+ * xs_fused_reduce_sgd with the record's values in place of hp's, and inv_loss_scale stays
+ * one value for the whole bucket.
+ */
+typedef struct {
+    float lr;
+    float momentum;
+    float weight_decay;
+    float reserved;          /* pads the record to 16 bytes; not read */
+} xs_tensor_hparams;
+
+/* xs_fused_reduce_sgd_mp with a record per tensor.  The replica buckets, params and momentum
+ * have the layout of gradient_plan (whose dtype is the gradients' and whose
+ * xs_plan_bucket_elems() is the element count); everything else as in xs_fused_reduce_sgd_mp.
+ *   tensor_hp   device, 16-byte aligned, xs_plan_n_tensors() records; read by the kernel, so
+ *               it must stay valid and unchanged until the pass has run.
+ */
+int xs_fused_reduce_sgd_pt(const xs_plan *gradient_plan, const void *const *replica_buckets,
+                           uint32_t W, float *params, float *momentum,
+                           float *params_out, float *momentum_out,
+                           const xs_tensor_hparams *tensor_hp, float inv_loss_scale,
+                           int32_t *found_inf, const xs_mp_options *mp, void *hip_stream);
+
+/* xs_fused_gather_reduce_sgd_mp with a record per tensor; tensor_hp as above. */
+int xs_fused_gather_reduce_sgd_pt(const xs_plan *gradient_plan, const void *const *grad_ptrs,
+                                  uint32_t W, float *params, float *momentum,
+                                  float *params_out, float *momentum_out,
+                                  void *const *param_tensor_ptrs,
+                                  const xs_tensor_hparams *tensor_hp, float inv_loss_scale,
+                                  int32_t *found_inf, const xs_mp_options *mp, void *hip_stream);
+
+/* ------------------------------------------------------------------------
  * Training task ("distributed task i" of Algorithm 1) as seen by the scheduler.
  * All pointers in the descriptor are copied or referenced as stated and must
  * stay valid until xs_app_destroy.
@@ -232,6 +268,8 @@ typedef struct {
     uint32_t flags;                          /* XS_APP_* bits                         */
     const void *const *grad_ptrs_tw;         /* device [n_tensors][W] table; required
                                                 with XS_APP_FUSED_GATHER, else may be NULL */
+    const xs_tensor_hparams *tensor_hp;      /* device, one record per tensor, or NULL:
+                                                hp's lr/momentum/weight_decay for all     */
 } xs_app_desc;
 
 /* Synchronise with xs_fused_gather_reduce_sgd (gradients read from the per-layer tensors,

@@ -302,11 +302,13 @@ static bool overlaps(const void *a, uint64_t a_bytes, const void *b, uint64_t b_
 
 static bool is_half_dtype(int dtype) { return dtype == XS_F16 || dtype == XS_BF16; }
 
-extern "C" int xs_fused_reduce_sgd_mp(const void *const *replica_buckets, uint32_t W, int grad_dtype,
-                                      uint64_t n_elems, float *params, float *momentum,
-                                      float *params_out, float *momentum_out,
-                                      const xs_sgd_hparams *hp, int32_t *found_inf,
-                                      const xs_mp_options *mp, void *hip_stream)
+// plan + tensor_hp: per-tensor records (both NULL for the single-triple entry points)
+static int reduce_sgd_checked(const xs_plan *plan, const xs_tensor_hparams *tensor_hp,
+                              const void *const *replica_buckets, uint32_t W, int grad_dtype,
+                              uint64_t n_elems, float *params, float *momentum,
+                              float *params_out, float *momentum_out,
+                              const xs_sgd_hparams *hp, int32_t *found_inf,
+                              const xs_mp_options *mp, void *hip_stream)
 {
     void *model_copy = mp ? mp->model_copy : nullptr;
     const int model_copy_dtype = mp ? mp->model_copy_dtype : XS_F16;
@@ -358,11 +360,47 @@ extern "C" int xs_fused_reduce_sgd_mp(const void *const *replica_buckets, uint32
             if (overlaps(model_copy, n_elems * 2, replica_buckets[w], gbytes))
                 return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd: model_copy overlaps replica_buckets[%u]", w);
     }
+    if (tensor_hp) {
+        const uint64_t hbytes = (uint64_t)plan->n_tensors * sizeof(xs_tensor_hparams);
+        for (int a = (out_of_place ? 2 : 0); a < n_state; ++a)
+            if (overlaps(tensor_hp, hbytes, state[a], sbytes))
+                return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd_pt: tensor_hp overlaps an output buffer");
+    }
     return launch_reduce_sgd(replica_buckets, W, grad_dtype, n_elems, params, momentum,
                              out_of_place ? params_out : params,
                              out_of_place ? momentum_out : momentum, *hp, found_inf,
                              /*detect=*/out_of_place && found_inf != nullptr, model_copy,
-                             model_copy_dtype, (hipStream_t)hip_stream);
+                             model_copy_dtype, tensor_hp ? plan : nullptr, tensor_hp,
+                             (hipStream_t)hip_stream);
+}
+
+extern "C" int xs_fused_reduce_sgd_mp(const void *const *replica_buckets, uint32_t W, int grad_dtype,
+                                      uint64_t n_elems, float *params, float *momentum,
+                                      float *params_out, float *momentum_out,
+                                      const xs_sgd_hparams *hp, int32_t *found_inf,
+                                      const xs_mp_options *mp, void *hip_stream)
+{
+    return reduce_sgd_checked(nullptr, nullptr, replica_buckets, W, grad_dtype, n_elems, params,
+                              momentum, params_out, momentum_out, hp, found_inf, mp, hip_stream);
+}
+
+// One (lr, momentum, weight decay) record per tensor of the plan the buckets were packed with.
+extern "C" int xs_fused_reduce_sgd_pt(const xs_plan *gradient_plan, const void *const *replica_buckets,
+                                      uint32_t W, float *params, float *momentum,
+                                      float *params_out, float *momentum_out,
+                                      const xs_tensor_hparams *tensor_hp, float inv_loss_scale,
+                                      int32_t *found_inf, const xs_mp_options *mp, void *hip_stream)
+{
+    if (!gradient_plan || gradient_plan->magic != XS_PLAN_MAGIC)
+        return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd_pt: plan is NULL or not a plan");
+    if (gradient_plan->bucket_elems == 0) return XS_OK;
+    if (!tensor_hp) return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd_pt: tensor_hp is NULL");
+    if (!aligned16(tensor_hp))
+        return fail(XS_ERR_ALIGNMENT, "xs_fused_reduce_sgd_pt: tensor_hp is not 16-byte aligned");
+    const xs_sgd_hparams hp = {0.f, 0.f, 0.f, inv_loss_scale};
+    return reduce_sgd_checked(gradient_plan, tensor_hp, replica_buckets, W, gradient_plan->dtype,
+                              gradient_plan->bucket_elems, params, momentum, params_out,
+                              momentum_out, &hp, found_inf, mp, hip_stream);
 }
 
 extern "C" int xs_fused_reduce_sgd(const void *const *replica_buckets, uint32_t W, int grad_dtype,
@@ -375,12 +413,12 @@ extern "C" int xs_fused_reduce_sgd(const void *const *replica_buckets, uint32_t 
 }
 
 // ---- the same pass reading the per-layer gradient tensors directly ----------------------
-extern "C" int xs_fused_gather_reduce_sgd_mp(const xs_plan *gradient_plan, const void *const *grad_ptrs,
-                                             uint32_t W, float *params, float *momentum,
-                                             float *params_out, float *momentum_out,
-                                             void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
-                                             int32_t *found_inf, const xs_mp_options *mp,
-                                             void *hip_stream)
+static int gather_reduce_sgd_checked(const xs_plan *gradient_plan, const void *const *grad_ptrs,
+                                     uint32_t W, float *params, float *momentum,
+                                     float *params_out, float *momentum_out,
+                                     void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
+                                     const xs_tensor_hparams *tensor_hp, int32_t *found_inf,
+                                     const xs_mp_options *mp, void *hip_stream)
 {
     const int view_dtype = mp ? mp->view_dtype : XS_F32;
     if (view_dtype != XS_F32 && !is_half_dtype(view_dtype))
@@ -420,10 +458,48 @@ extern "C" int xs_fused_gather_reduce_sgd_mp(const xs_plan *gradient_plan, const
         for (int b = a + 1; b < n_state; ++b)
             if (overlaps(state[a], sbytes, state[b], sbytes))
                 return fail(XS_ERR_INVALID_ARG, "xs_fused_gather_reduce_sgd: params/momentum buffers overlap");
+    if (tensor_hp) {
+        if (!aligned16(tensor_hp))
+            return fail(XS_ERR_ALIGNMENT, "xs_fused_gather_reduce_sgd_pt: tensor_hp is not 16-byte aligned");
+        const uint64_t hbytes = (uint64_t)gradient_plan->n_tensors * sizeof(xs_tensor_hparams);
+        for (int a = (out_of_place ? 2 : 0); a < n_state; ++a)
+            if (overlaps(tensor_hp, hbytes, state[a], sbytes))
+                return fail(XS_ERR_INVALID_ARG, "xs_fused_gather_reduce_sgd_pt: tensor_hp overlaps an output buffer");
+    }
     return launch_gather_reduce_sgd(gradient_plan, grad_ptrs, W, params, momentum,
                                     out_of_place ? params_out : params,
                                     out_of_place ? momentum_out : momentum, param_tensor_ptrs,
-                                    view_dtype, *hp, found_inf, detect, (hipStream_t)hip_stream);
+                                    view_dtype, *hp, tensor_hp, found_inf, detect,
+                                    (hipStream_t)hip_stream);
+}
+
+extern "C" int xs_fused_gather_reduce_sgd_mp(const xs_plan *gradient_plan, const void *const *grad_ptrs,
+                                             uint32_t W, float *params, float *momentum,
+                                             float *params_out, float *momentum_out,
+                                             void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
+                                             int32_t *found_inf, const xs_mp_options *mp,
+                                             void *hip_stream)
+{
+    return gather_reduce_sgd_checked(gradient_plan, grad_ptrs, W, params, momentum, params_out,
+                                     momentum_out, param_tensor_ptrs, hp, nullptr, found_inf, mp,
+                                     hip_stream);
+}
+
+extern "C" int xs_fused_gather_reduce_sgd_pt(const xs_plan *gradient_plan, const void *const *grad_ptrs,
+                                             uint32_t W, float *params, float *momentum,
+                                             float *params_out, float *momentum_out,
+                                             void *const *param_tensor_ptrs,
+                                             const xs_tensor_hparams *tensor_hp, float inv_loss_scale,
+                                             int32_t *found_inf, const xs_mp_options *mp,
+                                             void *hip_stream)
+{
+    if (gradient_plan && gradient_plan->magic == XS_PLAN_MAGIC && gradient_plan->bucket_elems != 0 &&
+        !tensor_hp)
+        return fail(XS_ERR_INVALID_ARG, "xs_fused_gather_reduce_sgd_pt: tensor_hp is NULL");
+    const xs_sgd_hparams hp = {0.f, 0.f, 0.f, inv_loss_scale};
+    return gather_reduce_sgd_checked(gradient_plan, grad_ptrs, W, params, momentum, params_out,
+                                     momentum_out, param_tensor_ptrs, &hp, tensor_hp, found_inf, mp,
+                                     hip_stream);
 }
 
 extern "C" int xs_fused_gather_reduce_sgd(const xs_plan *gradient_plan, const void *const *grad_ptrs,

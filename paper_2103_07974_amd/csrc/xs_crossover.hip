@@ -31,6 +31,7 @@ struct xs_app {
     const void *const *gather_table;   // device [T][W], fused-gather mode
     uint32_t flags;
     xs_sgd_hparams hp;
+    const xs_tensor_hparams *tensor_hp;   // device records per tensor, or nullptr
     int32_t *found_inf;
     xs_compute_fn compute;
     void *compute_ctx;
@@ -72,6 +73,8 @@ extern "C" int xs_app_create(const xs_app_desc *d, xs_app **out)
     if (!empty) {
         if (!aligned16(d->params) || !aligned16(d->momentum))
             return fail(XS_ERR_ALIGNMENT, "xs_app_create: params/momentum must be 16-byte aligned");
+        if (d->tensor_hp && !aligned16(d->tensor_hp))
+            return fail(XS_ERR_ALIGNMENT, "xs_app_create: tensor_hp must be 16-byte aligned");
         for (uint32_t w = 0; !gather && w < d->W; ++w) {
             if (!d->grad_tensor_ptrs[w] || !d->replica_buckets[w])
                 return fail(XS_ERR_INVALID_ARG, "xs_app_create: worker %u has a NULL table or bucket", w);
@@ -95,6 +98,7 @@ extern "C" int xs_app_create(const xs_app_desc *d, xs_app **out)
     a->momentum = d->momentum;
     a->param_table = d->param_tensor_ptrs;
     a->hp = d->hp;
+    a->tensor_hp = d->tensor_hp;
     a->found_inf = d->found_inf;
     a->compute = d->compute;
     a->compute_ctx = d->compute_ctx;
@@ -130,13 +134,24 @@ extern "C" int xs_app_destroy(xs_app *a)
 static int enqueue_sync(xs_app *a, hipStream_t s)
 {
     if (a->gplan->bucket_elems == 0) return XS_OK;
-    if (a->flags & XS_APP_FUSED_GATHER)
+    if (a->flags & XS_APP_FUSED_GATHER) {
+        if (a->tensor_hp)
+            return xs_fused_gather_reduce_sgd_pt(a->gplan, a->gather_table, a->W, a->params,
+                                                 a->momentum, nullptr, nullptr, a->param_table,
+                                                 a->tensor_hp, a->hp.inv_loss_scale, a->found_inf,
+                                                 nullptr, s);
         return xs_fused_gather_reduce_sgd(a->gplan, a->gather_table, a->W, a->params, a->momentum,
                                           nullptr, nullptr, a->param_table, &a->hp, a->found_inf, s);
+    }
     int rc = xs_fuse_pack_many(a->gplan, a->grad_tables.data(), a->buckets.data(), a->W,
                                a->found_inf, s);
     if (rc != XS_OK) return rc;
-    rc = xs_fused_reduce_sgd((const void *const *)a->buckets.data(), a->W, a->gplan->dtype,
+    if (a->tensor_hp)
+        rc = xs_fused_reduce_sgd_pt(a->gplan, (const void *const *)a->buckets.data(), a->W, a->params,
+                                    a->momentum, nullptr, nullptr, a->tensor_hp,
+                                    a->hp.inv_loss_scale, a->found_inf, nullptr, s);
+    else
+        rc = xs_fused_reduce_sgd((const void *const *)a->buckets.data(), a->W, a->gplan->dtype,
                                  a->gplan->bucket_elems, a->params, a->momentum, nullptr, nullptr,
                                  &a->hp, a->found_inf, s);
     if (rc != XS_OK) return rc;

@@ -78,6 +78,55 @@ __device__ __forceinline__ void sgd_update(float g_sum, float c, float &x, float
     x = x - lv;
 }
 
+// ---- hyper-parameters per tensor ----------------------------------------------------------
+// One 16-byte record (lr, momentum, weight decay, unused) per tensor; record t governs the
+// bucket elements offsets[t] .. offsets[t+1]-1 (tensor t and the padding behind it).
+struct TensorHp {
+    const f32x4 *rec;          // device [n_tensors], or nullptr: one triple for the bucket
+    const uint64_t *offsets;   // device [n_tensors + 1]
+    const uint32_t *row_first; // device [n_rows]: tensor whose segment holds a row's first element
+    uint32_t n_tensors;
+};
+
+// the tensor whose segment holds bucket element j; t must not be past it (forward search)
+__device__ __forceinline__ void seek_tensor(const TensorHp &h, uint32_t &t, uint64_t j)
+{
+    while (t + 1 < h.n_tensors && h.offsets[t + 1] <= j) ++t;
+}
+
+__device__ __forceinline__ void sgd_update4(const float *s, float c, f32x4 &x, f32x4 &v, f32x4 rec)
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        float xe = x[q], ve = v[q];
+        sgd_update(s[q], c, xe, ve, rec[0], rec[1], rec[2]);
+        x[q] = xe;
+        v[q] = ve;
+    }
+}
+
+// One 4-element state vector starting at bucket element j, which may span several segments
+// (tight layouts).  t as for seek_tensor; it is left at the tensor of the vector's first element.
+__device__ __forceinline__ void sgd_update4_per_tensor(const TensorHp &h, uint32_t &t, uint64_t j,
+                                                       const float *s, float c, f32x4 &x, f32x4 &v)
+{
+    seek_tensor(h, t, j);
+    if (j + 4 <= h.offsets[t + 1]) {
+        sgd_update4(s, c, x, v, h.rec[t]);
+        return;
+    }
+    uint32_t te = t;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        seek_tensor(h, te, j + q);
+        const f32x4 rec = h.rec[te];
+        float xe = x[q], ve = v[q];
+        sgd_update(s[q], c, xe, ve, rec[0], rec[1], rec[2]);
+        x[q] = xe;
+        v[q] = ve;
+    }
+}
+
 // ---- fp32 -> half-precision copies of the parameters (round to nearest even) ---------------
 __device__ __forceinline__ uint32_t to_f16_bits(float x)
 {

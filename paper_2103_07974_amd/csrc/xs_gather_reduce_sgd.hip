@@ -69,6 +69,7 @@ struct GatherArgs {
     const uintptr_t *param_ptrs;   // device [n_tensors] or nullptr
     int view_dtype;                // dtype of the views param_ptrs point to
     float lr, mu, wd, c;
+    const f32x4 *tensor_hp;        // device [n_tensors] records (lr, mu, wd, -), kernels with PT only
     int32_t *found_inf;
 };
 
@@ -77,7 +78,7 @@ struct GatherArgs {
 // state vectors `lane` and `64 + lane` of the row instead of the two under their own gradient
 // vector, and receive the matching gradient sums through the LDS crossbar, so that every
 // state access of the wavefront is one contiguous kilobyte.
-template <int W, int GT, bool DETECT, bool VIEWS, bool EXCH>
+template <int W, int GT, bool DETECT, bool VIEWS, bool PT, bool EXCH>
 __device__ __forceinline__ void vector_path(const GatherArgs &a, uint32_t t, uint64_t j, uint64_t k,
                                             bool &bad)
 {
@@ -108,19 +109,15 @@ __device__ __forceinline__ void vector_path(const GatherArgs &a, uint32_t t, uin
         x[q] = load16f<true>((const f32x4 *)(a.x_in + sj[q]));
         v[q] = load16f<true>((const f32x4 *)(a.v_in + sj[q]));
     }
+    // every state vector handled here lies in tensor t (EXCH: the whole row does)
+    const f32x4 rec = PT ? a.tensor_hp[t] : f32x4{a.lr, a.mu, a.wd, 0.f};
     float s[VEC];
 #pragma unroll
     for (int w = 0; w < W; ++w) accumulate<GT, DETECT>(g[w], w == 0, s, bad);
     if constexpr (EXCH) exchange_half_row(s);
 #pragma unroll
     for (int q = 0; q < SV; ++q) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float xe = x[q][e], ve = v[q][e];
-            sgd_update(s[4 * q + e], a.c, xe, ve, a.lr, a.mu, a.wd);
-            x[q][e] = xe;
-            v[q][e] = ve;
-        }
+        sgd_update4(s + 4 * q, a.c, x[q], v[q], rec);
         store16f<true>((f32x4 *)(a.x_out + sj[q]), x[q]);
         store16f<true>((f32x4 *)(a.v_out + sj[q]), v[q]);
     }
@@ -133,7 +130,7 @@ __device__ __forceinline__ void vector_path(const GatherArgs &a, uint32_t t, uin
 
 // One bucket element at a time: padding contributes +0, consecutive elements may belong to
 // different tensors.  `te` is carried along so that the search only ever moves forward.
-template <int GT, bool DETECT, bool VIEWS>
+template <int GT, bool DETECT, bool VIEWS, bool PT>
 __device__ __forceinline__ void element_path(const GatherArgs &a, uint32_t &te, uint64_t je, bool &bad)
 {
     constexpr int ES = Grad<GT>::ES;
@@ -153,7 +150,12 @@ __device__ __forceinline__ void element_path(const GatherArgs &a, uint32_t &te, 
         }
     }
     float xe = a.x_in[je], ve = a.v_in[je];
-    sgd_update(s, a.c, xe, ve, a.lr, a.mu, a.wd);
+    float lr = a.lr, mu = a.mu, wd = a.wd;
+    if constexpr (PT) {
+        const f32x4 rec = a.tensor_hp[te];     // padding follows the tensor in front of it
+        lr = rec[0]; mu = rec[1]; wd = rec[2];
+    }
+    sgd_update(s, a.c, xe, ve, lr, mu, wd);
     a.x_out[je] = xe;
     a.v_out[je] = ve;
     if constexpr (VIEWS) {
@@ -161,7 +163,7 @@ __device__ __forceinline__ void element_path(const GatherArgs &a, uint32_t &te, 
     }
 }
 
-template <int W, int GT, bool DETECT, bool VIEWS>
+template <int W, int GT, bool DETECT, bool VIEWS, bool PT>
 __global__ __launch_bounds__(kWave) void gather_reduce_sgd_kernel(GatherArgs a)
 {
     constexpr int VEC = 16 / Grad<GT>::ES;
@@ -184,16 +186,16 @@ __global__ __launch_bounds__(kWave) void gather_reduce_sgd_kernel(GatherArgs a)
             const uint32_t tu = (uint32_t)__builtin_amdgcn_readfirstlane((int)t_row);
             const uint64_t ku = j - a.tb.offsets[tu];
             if (Grad<GT>::HALF && (row + 1) * ROW <= a.n_bucket)      // complete row: all 64 lanes here
-                vector_path<W, GT, DETECT, VIEWS, Grad<GT>::HALF>(a, tu, j, ku, bad);
+                vector_path<W, GT, DETECT, VIEWS, PT, Grad<GT>::HALF>(a, tu, j, ku, bad);
             else
-                vector_path<W, GT, DETECT, VIEWS, false>(a, tu, j, ku, bad);
+                vector_path<W, GT, DETECT, VIEWS, PT, false>(a, tu, j, ku, bad);
         } else if (full) {
-            vector_path<W, GT, DETECT, VIEWS, false>(a, t, j, k, bad);
+            vector_path<W, GT, DETECT, VIEWS, PT, false>(a, t, j, k, bad);
         } else {
             uint32_t te = t;
             for (int e = 0; e < VEC; ++e) {
                 if (j + e >= a.n_bucket) break;
-                element_path<GT, DETECT, VIEWS>(a, te, j + e, bad);
+                element_path<GT, DETECT, VIEWS, PT>(a, te, j + e, bad);
             }
         }
     }
@@ -205,7 +207,7 @@ __global__ __launch_bounds__(kWave) void gather_reduce_sgd_kernel(GatherArgs a)
 }
 
 // Any W: element by element with a run-time replica count.
-template <int GT, bool DETECT, bool VIEWS>
+template <int GT, bool DETECT, bool VIEWS, bool PT>
 __global__ __launch_bounds__(kWave) void gather_reduce_sgd_anyw_kernel(GatherArgs a)
 {
     constexpr int VEC = 16 / Grad<GT>::ES;
@@ -218,7 +220,7 @@ __global__ __launch_bounds__(kWave) void gather_reduce_sgd_anyw_kernel(GatherArg
         uint32_t te = a.tb.row_first[row];
         for (int e = 0; e < VEC; ++e) {
             if (j + e >= a.n_bucket) break;
-            element_path<GT, DETECT, VIEWS>(a, te, j + e, bad);
+            element_path<GT, DETECT, VIEWS, PT>(a, te, j + e, bad);
         }
     }
     if constexpr (DETECT) {
@@ -228,47 +230,56 @@ __global__ __launch_bounds__(kWave) void gather_reduce_sgd_anyw_kernel(GatherArg
 }
 
 // ---- dispatch ---------------------------------------------------------------------------
-template <int W, int GT>
+template <int W, int GT, bool PT>
 static void launch_g(const GatherArgs &a, bool detect, bool views, dim3 grid, unsigned lds,
                      hipStream_t stream)
 {
     if (detect)
-        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, true, false>), grid, dim3(kWave), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, true, false, PT>), grid, dim3(kWave), lds, stream, a);
     else if (views)
-        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, false, true>), grid, dim3(kWave), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, false, true, PT>), grid, dim3(kWave), lds, stream, a);
     else
-        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, false, false>), grid, dim3(kWave), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, false, false, PT>), grid, dim3(kWave), lds, stream, a);
 }
 
-template <int GT>
+template <int GT, bool PT>
 static void launch_ganyw(const GatherArgs &a, bool detect, bool views, dim3 grid, unsigned lds,
                          hipStream_t stream)
 {
     if (detect)
-        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, true, false>), grid, dim3(kWave), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, true, false, PT>), grid, dim3(kWave), lds, stream, a);
     else if (views)
-        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, false, true>), grid, dim3(kWave), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, false, true, PT>), grid, dim3(kWave), lds, stream, a);
     else
-        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, false, false>), grid, dim3(kWave), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, false, false, PT>), grid, dim3(kWave), lds, stream, a);
+}
+
+template <int GT, bool PT>
+static void launch_w(const GatherArgs &a, bool detect, bool views, dim3 grid, unsigned lds,
+                     hipStream_t stream)
+{
+    switch (a.W) {
+    case 2: launch_g<2, GT, PT>(a, detect, views, grid, lds, stream); break;
+    case 4: launch_g<4, GT, PT>(a, detect, views, grid, lds, stream); break;
+    case 8: launch_g<8, GT, PT>(a, detect, views, grid, lds, stream); break;
+    case 16: launch_g<16, GT, PT>(a, detect, views, grid, lds, stream); break;
+    default: launch_ganyw<GT, PT>(a, detect, views, grid, lds, stream); break;
+    }
 }
 
 template <int GT>
 static void launch_gt(const GatherArgs &a, bool detect, bool views, dim3 grid, unsigned lds,
                       hipStream_t stream)
 {
-    switch (a.W) {
-    case 2: launch_g<2, GT>(a, detect, views, grid, lds, stream); break;
-    case 4: launch_g<4, GT>(a, detect, views, grid, lds, stream); break;
-    case 8: launch_g<8, GT>(a, detect, views, grid, lds, stream); break;
-    case 16: launch_g<16, GT>(a, detect, views, grid, lds, stream); break;
-    default: launch_ganyw<GT>(a, detect, views, grid, lds, stream); break;
-    }
+    if (a.tensor_hp != nullptr) launch_w<GT, true>(a, detect, views, grid, lds, stream);
+    else launch_w<GT, false>(a, detect, views, grid, lds, stream);
 }
 
 int launch_gather_reduce_sgd(const xs_plan *plan, const void *const *grad_ptrs, uint32_t W,
                              const float *x_in, const float *v_in, float *x_out, float *v_out,
                              void *const *param_ptrs, int view_dtype, const xs_sgd_hparams &hp,
-                             int32_t *found_inf, bool detect, hipStream_t stream)
+                             const xs_tensor_hparams *tensor_hp, int32_t *found_inf, bool detect,
+                             hipStream_t stream)
 {
     const int cus = compute_units();
     if (cus < 0) return cus;
@@ -286,6 +297,7 @@ int launch_gather_reduce_sgd(const xs_plan *plan, const void *const *grad_ptrs, 
     a.lr = hp.lr; a.mu = hp.momentum; a.wd = hp.weight_decay;
     volatile float one_over_w = 1.0f / (float)W;
     a.c = hp.inv_loss_scale * one_over_w;
+    a.tensor_hp = (const f32x4 *)tensor_hp;
     a.found_inf = found_inf;
 
     uint64_t blocks = plan->n_rows;

@@ -84,9 +84,13 @@ int launch_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_p
 int launch_gather_reduce_sgd(const xs_plan *plan, const void *const *grad_ptrs, uint32_t W,
                              const float *x_in, const float *v_in, float *x_out, float *v_out,
                              void *const *param_ptrs, int view_dtype, const xs_sgd_hparams &hp,
-                             int32_t *found_inf, bool detect, hipStream_t stream);
+                             const xs_tensor_hparams *tensor_hp, int32_t *found_inf, bool detect,
+                             hipStream_t stream);
 int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64_t n,
                       const float *x_in, const float *v_in, float *x_out, float *v_out,
                       const xs_sgd_hparams &hp, int32_t *found_inf, bool detect,
-                      void *model_copy, int model_copy_dtype, hipStream_t stream);
+                      void *model_copy, int model_copy_dtype, const xs_plan *plan,
+                      const xs_tensor_hparams *tensor_hp, hipStream_t stream);
+// plan + tensor_hp (both or neither): one (lr, momentum, weight decay) record per tensor of
+// the plan replaces hp's three; hp.inv_loss_scale always applies.
 }  // namespace xs

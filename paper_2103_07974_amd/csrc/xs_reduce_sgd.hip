@@ -38,10 +38,11 @@ struct ReduceArgs {
     int32_t *found_inf;
     void *model_copy;       // half-precision copy of the updated parameters, or nullptr
     int model_copy_dtype;   // XS_F16 or XS_BF16
+    TensorHp thp;           // per-tensor records (kernels with PT = true only)
 };
 
 // One element of the ragged tail (fewer than VEC elements at the end of the bucket).
-template <int GT, bool DETECT, typename Reps>
+template <int GT, bool DETECT, bool PT, typename Reps>
 __device__ __forceinline__ void tail_element(const Reps &reps, uint32_t W, const ReduceArgs &a,
                                              uint64_t j, bool &bad)
 {
@@ -55,15 +56,43 @@ __device__ __forceinline__ void tail_element(const Reps &reps, uint32_t W, const
         s = (w == 0) ? f : s + f;
     }
     float xe = a.x_in[j], ve = a.v_in[j];
-    sgd_update(s, a.c, xe, ve, a.lr, a.mu, a.wd);
+    float lr = a.lr, mu = a.mu, wd = a.wd;
+    if constexpr (PT) {
+        uint32_t t = a.thp.row_first[j / ((uint64_t)kThreads * (16 / Grad<GT>::ES))];
+        seek_tensor(a.thp, t, j);
+        const f32x4 rec = a.thp.rec[t];
+        lr = rec[0]; mu = rec[1]; wd = rec[2];
+    }
+    sgd_update(s, a.c, xe, ve, lr, mu, wd);
     a.x_out[j] = xe;
     a.v_out[j] = ve;
     if (a.model_copy) ((uint16_t *)a.model_copy)[j] = to_half1(xe, a.model_copy_dtype);
 }
 
+// The state vectors of one row of kThreads gradient vectors under per-tensor records: the
+// row's first tensor and, when the whole row lies in that tensor's segment (the rule: the
+// smallest layers of the workloads are a quarter of a row), its record through scalar loads.
+struct RowHp {
+    uint32_t t_first;
+    bool uniform;
+    f32x4 rec;
+};
+template <int VEC>
+__device__ __forceinline__ RowHp row_hp(const TensorHp &h, uint64_t first_vec, uint64_t n)
+{
+    constexpr uint64_t ROW = (uint64_t)kThreads * VEC;
+    const uint32_t row = (uint32_t)__builtin_amdgcn_readfirstlane((int)(first_vec / kThreads));
+    RowHp r;
+    r.t_first = h.row_first[row];
+    const uint64_t row_end = ((uint64_t)row + 1) * ROW < n ? ((uint64_t)row + 1) * ROW : n;
+    r.uniform = h.offsets[r.t_first + 1] >= row_end;
+    r.rec = h.rec[r.t_first];
+    return r;
+}
+
 // VEC elements per lane per trip: 4 (fp32 gradients) or 8 (fp16 / bf16 gradients), so that
 // every gradient load is 16 bytes wide.
-template <int W, int GT, bool DETECT, bool NTG, bool NTS>
+template <int W, int GT, bool DETECT, bool NTG, bool NTS, bool PT>
 __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(ReplicaPtrs<W> reps, ReduceArgs a)
 {
     constexpr bool HALF = Grad<GT>::HALF;
@@ -101,21 +130,20 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(ReplicaPtrs<W> rep
             x[k] = load16f<NTS>((const f32x4 *)a.x_in + sx[k]);
             v[k] = load16f<NTS>((const f32x4 *)a.v_in + sx[k]);
         }
+        RowHp rh;
+        if constexpr (PT) rh = row_hp<VEC>(a.thp, i - threadIdx.x, a.n);
+        else rh.rec = f32x4{a.lr, a.mu, a.wd, 0.f};
         float s[VEC];
 #pragma unroll
         for (int w = 0; w < W; ++w) accumulate<GT, DETECT>(g[w], w == 0, s, bad);
         if constexpr (HALF) {
             if (exchanged) exchange_half_row(s);
         }
+        uint32_t t = PT ? rh.t_first : 0u;
 #pragma unroll
         for (int k = 0; k < SV; ++k) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float xe = x[k][q], ve = v[k][q];
-                sgd_update(s[4 * k + q], a.c, xe, ve, a.lr, a.mu, a.wd);
-                x[k][q] = xe;
-                v[k][q] = ve;
-            }
+            if (!PT || rh.uniform) sgd_update4(s + 4 * k, a.c, x[k], v[k], rh.rec);
+            else sgd_update4_per_tensor(a.thp, t, sx[k] * 4, s + 4 * k, a.c, x[k], v[k]);
             store16f<NTS>((f32x4 *)a.x_out + sx[k], x[k]);
             store16f<NTS>((f32x4 *)a.v_out + sx[k], v[k]);
             if (a.model_copy)
@@ -126,7 +154,7 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(ReplicaPtrs<W> rep
     // ragged tail: fewer than VEC elements, one lane each, in workgroup 0
     const uint32_t rem = (uint32_t)(a.n - nvec * VEC);
     if (blockIdx.x == 0 && threadIdx.x < rem)
-        tail_element<GT, DETECT>(reps, (uint32_t)W, a, nvec * VEC + threadIdx.x, bad);
+        tail_element<GT, DETECT, PT>(reps, (uint32_t)W, a, nvec * VEC + threadIdx.x, bad);
 
     if constexpr (DETECT) {
         // wavefront-level vote, then at most one atomic per wavefront
@@ -137,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(ReplicaPtrs<W> rep
 
 // Any W up to XS_MAX_REPLICAS: replica loop with a run-time trip count, four loads in flight
 // at a time.  Same arithmetic and order as the specialised kernels; plain lane mapping.
-template <int GT, bool DETECT>
+template <int GT, bool DETECT, bool PT>
 __global__ __launch_bounds__(kThreads) void reduce_sgd_anyw_kernel(
     ReplicaPtrs<XS_MAX_REPLICAS> reps, uint32_t W, ReduceArgs a)
 {
@@ -149,21 +177,20 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_anyw_kernel(
     const uint64_t stride = (uint64_t)gridDim.x * kThreads;
     bool bad = false;
     for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
+        RowHp rh;
+        if constexpr (PT) rh = row_hp<VEC>(a.thp, i - threadIdx.x, a.n);
+        else rh.rec = f32x4{a.lr, a.mu, a.wd, 0.f};
         float s[VEC];
         accumulate<GT, DETECT>(*((const u32x4 *)reps.p[0] + i), true, s, bad);
 #pragma unroll 4
         for (uint32_t w = 1; w < W; ++w)
             accumulate<GT, DETECT>(*((const u32x4 *)reps.p[w] + i), false, s, bad);
+        uint32_t t = PT ? rh.t_first : 0u;
 #pragma unroll
         for (int k = 0; k < SV; ++k) {
             f32x4 x = ((const f32x4 *)a.x_in)[i * SV + k], v = ((const f32x4 *)a.v_in)[i * SV + k];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float xe = x[q], ve = v[q];
-                sgd_update(s[4 * k + q], a.c, xe, ve, a.lr, a.mu, a.wd);
-                x[q] = xe;
-                v[q] = ve;
-            }
+            if (!PT || rh.uniform) sgd_update4(s + 4 * k, a.c, x, v, rh.rec);
+            else sgd_update4_per_tensor(a.thp, t, (i * SV + k) * 4, s + 4 * k, a.c, x, v);
             ((f32x4 *)a.x_out)[i * SV + k] = x;
             ((f32x4 *)a.v_out)[i * SV + k] = v;
             if (a.model_copy) ((u32x2 *)a.model_copy)[i * SV + k] = to_half4(x, a.model_copy_dtype);
@@ -171,7 +198,7 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_anyw_kernel(
     }
     const uint32_t rem = (uint32_t)(a.n - nvec * VEC);
     if (blockIdx.x == 0 && threadIdx.x < rem)
-        tail_element<GT, DETECT>(reps, W, a, nvec * VEC + threadIdx.x, bad);
+        tail_element<GT, DETECT, PT>(reps, W, a, nvec * VEC + threadIdx.x, bad);
     if constexpr (DETECT) {
         if (__builtin_amdgcn_ballot_w64(bad) != 0ull && (threadIdx.x & 63u) == 0u)
             atomicOr(a.found_inf, 1);
@@ -187,20 +214,27 @@ struct Launch {
     hipStream_t stream;
 };
 
-template <int W, int GT, bool DETECT, bool NTG, bool NTS>
+template <int W, int GT, bool DETECT, bool NTG, bool NTS, bool PT>
 static void launch_one(const Launch &l)
 {
     ReplicaPtrs<W> r;
     for (int w = 0; w < W; ++w) r.p[w] = l.replicas[w];
-    hipLaunchKernelGGL((reduce_sgd_kernel<W, GT, DETECT, NTG, NTS>), l.grid, dim3(kThreads),
+    hipLaunchKernelGGL((reduce_sgd_kernel<W, GT, DETECT, NTG, NTS, PT>), l.grid, dim3(kThreads),
                        l.lds_reserve, l.stream, r, l.a);
+}
+
+template <int W, int GT, bool DETECT, bool NTG, bool NTS>
+static void launch_pt(const Launch &l)
+{
+    if (l.a.thp.rec != nullptr) launch_one<W, GT, DETECT, NTG, NTS, true>(l);
+    else launch_one<W, GT, DETECT, NTG, NTS, false>(l);
 }
 
 template <int W, int GT, bool DETECT>
 static void launch_nt(const Launch &l, bool ntg, bool nts)
 {
-    if (ntg) { if (nts) launch_one<W, GT, DETECT, true, true>(l); else launch_one<W, GT, DETECT, true, false>(l); }
-    else     { if (nts) launch_one<W, GT, DETECT, false, true>(l); else launch_one<W, GT, DETECT, false, false>(l); }
+    if (ntg) { if (nts) launch_pt<W, GT, DETECT, true, true>(l); else launch_pt<W, GT, DETECT, true, false>(l); }
+    else     { if (nts) launch_pt<W, GT, DETECT, false, true>(l); else launch_pt<W, GT, DETECT, false, false>(l); }
 }
 
 template <int W, int GT>
@@ -220,23 +254,28 @@ static void launch_w(const Launch &l, int dtype, bool detect, bool ntg, bool nts
     }
 }
 
-template <int GT>
-static void launch_anyw(const Launch &l, uint32_t W, bool detect)
+template <int GT, bool DETECT, bool PT>
+static void launch_anyw_one(const Launch &l, uint32_t W)
 {
     ReplicaPtrs<XS_MAX_REPLICAS> r;
     for (uint32_t w = 0; w < XS_MAX_REPLICAS; ++w) r.p[w] = w < W ? l.replicas[w] : nullptr;
-    if (detect)
-        hipLaunchKernelGGL((reduce_sgd_anyw_kernel<GT, true>), l.grid, dim3(kThreads), l.lds_reserve,
-                           l.stream, r, W, l.a);
-    else
-        hipLaunchKernelGGL((reduce_sgd_anyw_kernel<GT, false>), l.grid, dim3(kThreads), l.lds_reserve,
-                           l.stream, r, W, l.a);
+    hipLaunchKernelGGL((reduce_sgd_anyw_kernel<GT, DETECT, PT>), l.grid, dim3(kThreads), l.lds_reserve,
+                       l.stream, r, W, l.a);
+}
+
+template <int GT>
+static void launch_anyw(const Launch &l, uint32_t W, bool detect)
+{
+    const bool pt = l.a.thp.rec != nullptr;
+    if (detect) { if (pt) launch_anyw_one<GT, true, true>(l, W); else launch_anyw_one<GT, true, false>(l, W); }
+    else        { if (pt) launch_anyw_one<GT, false, true>(l, W); else launch_anyw_one<GT, false, false>(l, W); }
 }
 
 int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64_t n,
                       const float *x_in, const float *v_in, float *x_out, float *v_out,
                       const xs_sgd_hparams &hp, int32_t *found_inf, bool detect,
-                      void *model_copy, int model_copy_dtype, hipStream_t stream)
+                      void *model_copy, int model_copy_dtype, const xs_plan *plan,
+                      const xs_tensor_hparams *tensor_hp, hipStream_t stream)
 {
     const int cus = compute_units();
     if (cus < 0) return cus;
@@ -263,6 +302,11 @@ int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64
     l.a.found_inf = found_inf;
     l.a.model_copy = model_copy;
     l.a.model_copy_dtype = model_copy_dtype;
+    // per-tensor records need the layout (plan) that the buckets were packed with
+    l.a.thp.rec = (plan && tensor_hp) ? (const f32x4 *)tensor_hp : nullptr;
+    l.a.thp.offsets = plan ? plan->tables.offsets : nullptr;
+    l.a.thp.row_first = plan ? plan->tables.row_first : nullptr;
+    l.a.thp.n_tensors = plan ? plan->n_tensors : 0;
     l.grid = dim3((unsigned)blocks);
     l.stream = stream;
     // Measured on MI355X: the pass is fastest with 10 one-wave workgroups per compute unit

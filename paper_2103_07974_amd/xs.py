@@ -47,7 +47,8 @@ EXPORTS = [
     "xs_plan_bucket_elems", "xs_plan_n_tensors", "xs_fuse_pack", "xs_fuse_pack_many",
     "xs_fuse_unpack",
     "xs_fused_reduce_sgd", "xs_fused_reduce_sgd_mp", "xs_fused_gather_reduce_sgd",
-    "xs_fused_gather_reduce_sgd_mp", "xs_app_create", "xs_app_destroy", "xs_app_sync", "xs_crossover_step",
+    "xs_fused_gather_reduce_sgd_mp", "xs_fused_reduce_sgd_pt", "xs_fused_gather_reduce_sgd_pt",
+    "xs_app_create", "xs_app_destroy", "xs_app_sync", "xs_crossover_step",
     "xs_crossover_drain", "xs_app_wait_sync", "xs_tuning_set", "xs_tuning_get", "xs_standin_alu",
 ]
 
@@ -80,7 +81,8 @@ class AppDesc(ctypes.Structure):
                 ("param_tensor_ptrs", ctypes.c_void_p),
                 ("hp", SgdHparams), ("found_inf", ctypes.c_void_p),
                 ("compute", COMPUTE_FN), ("compute_ctx", ctypes.c_void_p),
-                ("flags", ctypes.c_uint32), ("grad_ptrs_tw", ctypes.c_void_p)]
+                ("flags", ctypes.c_uint32), ("grad_ptrs_tw", ctypes.c_void_p),
+                ("tensor_hp", ctypes.c_void_p)]
 
 
 XS_APP_FUSED_GATHER = 1
@@ -122,6 +124,10 @@ def lib() -> ctypes.CDLL:
     L.xs_fused_gather_reduce_sgd_mp.argtypes = [vp, vp, ctypes.c_uint32, vp, vp, vp, vp, vp,
                                                 ctypes.POINTER(SgdHparams), vp,
                                                 ctypes.POINTER(MpOptions), vp]
+    L.xs_fused_reduce_sgd_pt.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_uint32, vp, vp, vp, vp, vp,
+                                         ctypes.c_float, vp, ctypes.POINTER(MpOptions), vp]
+    L.xs_fused_gather_reduce_sgd_pt.argtypes = [vp, vp, ctypes.c_uint32, vp, vp, vp, vp, vp, vp,
+                                                ctypes.c_float, vp, ctypes.POINTER(MpOptions), vp]
     L.xs_app_create.argtypes = [ctypes.POINTER(AppDesc), ctypes.POINTER(vp)]
     L.xs_app_destroy.argtypes = [vp]
     L.xs_app_sync.argtypes = [vp, vp]
@@ -316,6 +322,52 @@ def fused_gather_reduce_sgd(plan: Plan, grad_ptrs: torch.Tensor, W: int, params:
                                                _stream_ptr(stream)), "xs_fused_gather_reduce_sgd_mp")
 
 
+def tensor_hparams_table(tensor_hp: Sequence[Sequence[float]], device=None) -> torch.Tensor:
+    """Device array of xs_tensor_hparams records: tensor_hp[t] = (lr, momentum, weight_decay)."""
+    rows = [[float(lr), float(mu), float(wd), 0.0] for lr, mu, wd in tensor_hp]
+    t = torch.tensor(rows if rows else [[0.0] * 4], dtype=torch.float32)
+    return t.to(device if device is not None else torch.device("cuda"))
+
+
+def fused_reduce_sgd_pt(plan: Plan, replica_buckets: Sequence[torch.Tensor], params: torch.Tensor,
+                        momentum: torch.Tensor, tensor_hp: torch.Tensor,
+                        inv_loss_scale: float = 1.0, params_out: Optional[torch.Tensor] = None,
+                        momentum_out: Optional[torch.Tensor] = None,
+                        found_inf: Optional[torch.Tensor] = None, stream=None,
+                        model_copy: Optional[torch.Tensor] = None) -> None:
+    """Bucket form with one (lr, momentum, weight decay) record per tensor of `plan`
+    (tensor_hp: device table from tensor_hparams_table)."""
+    W = len(replica_buckets)
+    arr = (ctypes.c_void_p * max(W, 1))(*[_dptr(b) for b in replica_buckets])
+    mp = None
+    if model_copy is not None:
+        mp = ctypes.byref(MpOptions(_dptr(model_copy), dtype_code(model_copy.dtype), XS_F32))
+    _check(lib().xs_fused_reduce_sgd_pt(plan.handle, arr, W, _dptr(params), _dptr(momentum),
+                                        _dptr(params_out), _dptr(momentum_out), _dptr(tensor_hp),
+                                        float(inv_loss_scale), _dptr(found_inf), mp,
+                                        _stream_ptr(stream)), "xs_fused_reduce_sgd_pt")
+
+
+def fused_gather_reduce_sgd_pt(plan: Plan, grad_ptrs: torch.Tensor, W: int, params: torch.Tensor,
+                               momentum: torch.Tensor, tensor_hp: torch.Tensor,
+                               inv_loss_scale: float = 1.0,
+                               params_out: Optional[torch.Tensor] = None,
+                               momentum_out: Optional[torch.Tensor] = None,
+                               param_tensor_ptrs: Optional[torch.Tensor] = None,
+                               found_inf: Optional[torch.Tensor] = None, stream=None,
+                               view_dtype: torch.dtype = torch.float32) -> None:
+    """Gathering form with one (lr, momentum, weight decay) record per tensor of `plan`."""
+    mp = None
+    if view_dtype != torch.float32:
+        mp = ctypes.byref(MpOptions(None, XS_F16, dtype_code(view_dtype)))
+    _check(lib().xs_fused_gather_reduce_sgd_pt(plan.handle, _dptr(grad_ptrs), int(W), _dptr(params),
+                                               _dptr(momentum), _dptr(params_out),
+                                               _dptr(momentum_out), _dptr(param_tensor_ptrs),
+                                               _dptr(tensor_hp), float(inv_loss_scale),
+                                               _dptr(found_inf), mp, _stream_ptr(stream)),
+           "xs_fused_gather_reduce_sgd_pt")
+
+
 # ---------------------------------------------------------------- crossover
 class App:
     """Owner of an xs_app handle; keeps every buffer the handle refers to alive."""
@@ -325,12 +377,14 @@ class App:
                  params: torch.Tensor, momentum: torch.Tensor, param_table: torch.Tensor,
                  lr: float, mu: float, wd: float, inv_loss_scale: float = 1.0,
                  found_inf: Optional[torch.Tensor] = None, compute=None,
-                 gather_table: Optional[torch.Tensor] = None, W: Optional[int] = None):
+                 gather_table: Optional[torch.Tensor] = None, W: Optional[int] = None,
+                 tensor_hp: Optional[torch.Tensor] = None):
         """With gather_table (device [tensor][worker] addresses) the app synchronises with the
-        gathering kernel; grad_tables and replica_buckets may then be empty and W must be given."""
+        gathering kernel; grad_tables and replica_buckets may then be empty and W must be given.
+        tensor_hp (device table from tensor_hparams_table) replaces lr/mu/wd per tensor."""
         W = len(replica_buckets) if W is None else W
         self._keep = (gradient_plan, parameter_plan, list(grad_tables), list(replica_buckets),
-                      params, momentum, param_table, found_inf, gather_table)
+                      params, momentum, param_table, found_inf, gather_table, tensor_hp)
         self._tables = (ctypes.c_void_p * max(len(grad_tables), 1))(*[_dptr(t) for t in grad_tables])
         self._buckets = (ctypes.c_void_p * max(len(replica_buckets), 1))(*[_dptr(b) for b in replica_buckets])
         if compute is not None:
@@ -354,6 +408,7 @@ class App:
         d.compute_ctx = None
         d.flags = XS_APP_FUSED_GATHER if gather_table is not None else 0
         d.grad_ptrs_tw = _dptr(gather_table)
+        d.tensor_hp = _dptr(tensor_hp)
         h = ctypes.c_void_p()
         _check(lib().xs_app_create(ctypes.byref(d), ctypes.byref(h)), "xs_app_create")
         self.handle = h
