@@ -126,6 +126,40 @@ def time_gather(tasks, stream, reps=30, warm=6):
             "GBs_by_headline_formula": tasks[0].reduce_bytes() / ms / 1e6}
 
 
+def time_param_groups(tasks, stream, reps=30, warm=6):
+    """Both forms with one (lr, momentum, weight decay) record per tensor: weight decay on
+    matrices and filters only, biases and normalisation parameters in a group of their own.
+    Same bytes as the single-triple forms plus a 16-byte record per tensor."""
+    import torch
+    from paper_2103_07974_amd import xs
+    w = tasks[0].workload
+    table = xs.tensor_hparams_table([(w.lr, w.momentum, w.weight_decay) if len(s) > 1
+                                     else (2 * w.lr, w.momentum, 0.0) for s in w.shapes])
+    out = {}
+    for form in ("bucket", "gather"):
+        ts = []
+        with torch.cuda.stream(stream):
+            for i in range(warm + reps):
+                t = tasks[i % len(tasks)]
+                a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+                a.record(stream)
+                if form == "bucket":
+                    xs.fused_reduce_sgd_pt(t.gplan, t.buckets, t.params, t.momentum, table,
+                                           1.0 / w.loss_scale, stream=stream)
+                else:
+                    xs.fused_gather_reduce_sgd_pt(t.gplan, t.gather_table, w.W, t.params, t.momentum,
+                                                  table, 1.0 / w.loss_scale,
+                                                  param_tensor_ptrs=t.param_table, stream=stream)
+                b.record(stream); b.synchronize()
+                if i >= warm:
+                    ts.append(a.elapsed_time(b))
+        ms = _median(ts)
+        nbytes = tasks[0].reduce_bytes() if form == "bucket" else tasks[0].gather_bytes(True)
+        out[form + "_form"] = {"ms": ms, "GBs": nbytes / ms / 1e6,
+                               "frac_of_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBS}
+    return out
+
+
 def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False, standin="gemm",
                    cross_only=False):
     """Two tasks alternate as in Algorithm 1: one computes (a stand-in for forward + backward)
@@ -373,6 +407,7 @@ def main():
     }
     extra = {"resnet50": time_kernels(tasks[0], stream)}
     extra["resnet50"]["gather_form"] = time_gather(tasks, stream)
+    extra["resnet50"]["param_groups"] = time_param_groups(tasks, stream)
     del tasks
     torch.cuda.empty_cache()
 
@@ -416,6 +451,7 @@ def main():
         bert = harness.make_task(wl.BERT_LARGE_F16, "cuda")
         extra["bert_large_f16"] = time_kernels(bert, stream, reps=15, warm=3)
         extra["bert_large_f16"]["gather_form"] = time_gather([bert], stream, reps=10, warm=2)
+        extra["bert_large_f16"]["param_groups"] = time_param_groups([bert], stream, reps=10, warm=2)
         del bert
         torch.cuda.empty_cache()
 
