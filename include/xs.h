@@ -299,6 +299,22 @@ int xs_crossover_step(xs_app *compute_app, xs_app *sync_app,
  * synchronises app's outstanding gradients on sync_stream.  XS_ERR_STATE if none. */
 int xs_crossover_drain(xs_app *app, void *sync_stream);
 
+/* One outer iteration of Algorithm 1 over N tasks ("for i = 1..N"): apps[i] computes while
+ * the task of the previous inner step (apps[i-1]; apps[N-1] of the previous call for i = 0)
+ * is synchronised, if its gradients are outstanding - they are not at the very first inner
+ * step (the bypass of Section 2.2).  Every synchronisation thus has the N-1 computations that
+ * follow it to hide under before its own task computes again.  n_apps == 1 degenerates to
+ * compute, then synchronise.  The same array, in the same order, is expected on every call.
+ * Enqueue only; stops at the first error and returns it.
+ */
+int xs_crossover_iteration(xs_app *const *apps, uint32_t n_apps,
+                           void *compute_stream, void *sync_stream);
+
+/* The additional synchronisation phase after the last iteration for N tasks: synchronises
+ * every app of the array whose gradients are still outstanding, in array order.  XS_OK if
+ * none is. */
+int xs_crossover_finish(xs_app *const *apps, uint32_t n_apps, void *sync_stream);
+
 /* Makes hip_stream wait for app's last enqueued synchronisation (no-op if none). */
 int xs_app_wait_sync(xs_app *app, void *hip_stream);
 

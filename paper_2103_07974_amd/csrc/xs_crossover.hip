@@ -214,6 +214,44 @@ extern "C" int xs_crossover_drain(xs_app *a, void *sync_stream)
     return sync_on_stream(a, (hipStream_t)sync_stream);
 }
 
+// Algorithm 1, the inner loop "for i = 1..N" of one outer iteration.
+extern "C" int xs_crossover_iteration(xs_app *const *apps, uint32_t n_apps, void *compute_stream,
+                                      void *sync_stream)
+{
+    if (n_apps == 0) return XS_OK;
+    if (!apps) return fail(XS_ERR_INVALID_ARG, "xs_crossover_iteration: apps is NULL");
+    for (uint32_t i = 0; i < n_apps; ++i) {
+        if (!is_app(apps[i]))
+            return fail(XS_ERR_INVALID_ARG, "xs_crossover_iteration: apps[%u] is NULL or not an app", i);
+        for (uint32_t k = 0; k < i; ++k)
+            if (apps[k] == apps[i])
+                return fail(XS_ERR_INVALID_ARG, "xs_crossover_iteration: apps[%u] and apps[%u] are the same app", k, i);
+    }
+    for (uint32_t i = 0; i < n_apps; ++i) {
+        xs_app *x = apps[i];
+        xs_app *y = n_apps == 1 ? x : apps[(i + n_apps - 1) % n_apps];
+        if (y != x && !y->grads_outstanding) y = nullptr;      // first-iteration bypass
+        const int rc = xs_crossover_step(x, y, compute_stream, sync_stream);
+        if (rc != XS_OK) return rc;
+    }
+    return XS_OK;
+}
+
+extern "C" int xs_crossover_finish(xs_app *const *apps, uint32_t n_apps, void *sync_stream)
+{
+    if (n_apps == 0) return XS_OK;
+    if (!apps) return fail(XS_ERR_INVALID_ARG, "xs_crossover_finish: apps is NULL");
+    for (uint32_t i = 0; i < n_apps; ++i)
+        if (!is_app(apps[i]))
+            return fail(XS_ERR_INVALID_ARG, "xs_crossover_finish: apps[%u] is NULL or not an app", i);
+    for (uint32_t i = 0; i < n_apps; ++i) {
+        if (!apps[i]->grads_outstanding) continue;
+        const int rc = sync_on_stream(apps[i], (hipStream_t)sync_stream);
+        if (rc != XS_OK) return rc;
+    }
+    return XS_OK;
+}
+
 extern "C" int xs_app_wait_sync(xs_app *a, void *hip_stream)
 {
     if (!is_app(a)) return fail(XS_ERR_INVALID_ARG, "xs_app_wait_sync: app is NULL or not an app");

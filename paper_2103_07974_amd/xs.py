@@ -49,7 +49,7 @@ EXPORTS = [
     "xs_fused_reduce_sgd", "xs_fused_reduce_sgd_mp", "xs_fused_gather_reduce_sgd",
     "xs_fused_gather_reduce_sgd_mp", "xs_fused_reduce_sgd_pt", "xs_fused_gather_reduce_sgd_pt",
     "xs_app_create", "xs_app_destroy", "xs_app_sync", "xs_crossover_step",
-    "xs_crossover_drain", "xs_app_wait_sync", "xs_tuning_set", "xs_tuning_get", "xs_standin_alu",
+    "xs_crossover_drain", "xs_crossover_iteration", "xs_crossover_finish", "xs_app_wait_sync", "xs_tuning_set", "xs_tuning_get", "xs_standin_alu",
 ]
 
 
@@ -134,6 +134,8 @@ def lib() -> ctypes.CDLL:
     L.xs_crossover_step.argtypes = [vp, vp, vp, vp]
     L.xs_crossover_drain.argtypes = [vp, vp]
     L.xs_app_wait_sync.argtypes = [vp, vp]
+    L.xs_crossover_iteration.argtypes = [ctypes.POINTER(vp), ctypes.c_uint32, vp, vp]
+    L.xs_crossover_finish.argtypes = [ctypes.POINTER(vp), ctypes.c_uint32, vp]
     L.xs_standin_alu.argtypes = [ctypes.c_uint32, ctypes.c_uint32, vp, vp]
     L.xs_tuning_set.argtypes = [ctypes.c_int, ctypes.c_int]
     L.xs_tuning_get.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
@@ -439,6 +441,22 @@ def crossover_step(compute_app: App, sync_app: Optional[App], compute_stream, sy
 
 def crossover_drain(app: App, sync_stream) -> None:
     _check(lib().xs_crossover_drain(app.handle, _stream_ptr(sync_stream)), "xs_crossover_drain")
+
+
+def _app_array(apps: Sequence[App]):
+    return (ctypes.c_void_p * max(len(apps), 1))(*[a.handle.value for a in apps])
+
+
+def crossover_iteration(apps: Sequence[App], compute_stream, sync_stream) -> None:
+    """One outer iteration of Algorithm 1 over all tasks of `apps`."""
+    _check(lib().xs_crossover_iteration(_app_array(apps), len(apps), _stream_ptr(compute_stream),
+                                        _stream_ptr(sync_stream)), "xs_crossover_iteration")
+
+
+def crossover_finish(apps: Sequence[App], sync_stream) -> None:
+    """The final synchronisation phase: every task with gradients still outstanding."""
+    _check(lib().xs_crossover_finish(_app_array(apps), len(apps), _stream_ptr(sync_stream)),
+           "xs_crossover_finish")
 
 
 def standin_alu(workgroups: int, iters: int, sink: torch.Tensor, stream=None) -> None:

@@ -114,6 +114,43 @@ def test_three_tasks_match_algorithm_1():
         a.destroy()
 
 
+def _run_gpu_iterations(workloads, T, align, fused_gather=False):
+    """The same schedule through the library's own N-task loop."""
+    tasks = [harness.make_task(w, "cuda", align) for w in workloads]
+    counters = [[0] for _ in tasks]
+    apps = [t.make_app(_device_compute(t, c), fused_gather=fused_gather)
+            for t, c in zip(tasks, counters)]
+    cs, ss = torch.cuda.Stream(), torch.cuda.Stream()
+    for _ in range(T):
+        xs.crossover_iteration(apps, cs, ss)
+    xs.crossover_finish(apps, ss)
+    xs.crossover_finish(apps, ss)          # nothing outstanding any more: a no-op
+    torch.cuda.synchronize()
+    return tasks, apps, counters
+
+
+@pytest.mark.parametrize("N,fused_gather", [(1, False), (2, False), (3, True), (4, False), (4, True)])
+def test_library_iteration_loop_matches_algorithm_1(N, fused_gather):
+    shapes = [[(300, 7), (64,)], [(17,), (900, 3)], [(5000,), (3,), (128,)], [(2048,), (1,)]]
+    Ws = [2, 4, 3, 8]
+    wls = [_mini("abcd"[i], shapes[i], W=Ws[i]) for i in range(N)]
+    T = 3
+    tasks, apps, counters = _run_gpu_iterations(wls, T, align=4, fused_gather=fused_gather)
+    state, log = _run_oracle(wls, T, 4, tasks)
+    assert [c[0] for c in counters] == [T] * N
+    assert sum(1 for e in log if e[0] in ("update", "drain")) == N * T
+    for i, task in enumerate(tasks):
+        for got, want in zip(task.param_tensors, state["p"][i]):
+            assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
+        assert np.array_equal(task.momentum.cpu().numpy().view(np.uint32),
+                              state["v"][i].view(np.uint32))
+    with pytest.raises(xs.XsError) as e:
+        xs.crossover_iteration([apps[0], apps[0]], torch.cuda.Stream(), torch.cuda.Stream())
+    assert e.value.status == xs.XS_ERR_INVALID_ARG
+    for a in apps:
+        a.destroy()
+
+
 def test_single_task_degenerates_to_compute_then_sync():
     wls = [_mini("solo", [(1000,), (33,)], W=2)]
     tasks, apps, counters = _run_gpu(wls, 3, align=4)

@@ -30,6 +30,20 @@ def test_own_ratio_below_one_is_not_enough():
     assert tl.stall == pytest.approx(len(per_step) * (3.0 - 1.0))
 
 
+def test_three_tasks_relax_the_condition_to_the_other_tasks_total_compute():
+    # with N tasks a synchronisation has the N-1 computations that follow it to hide under:
+    # M_0 may exceed every single C_j as long as it fits under their sum (channel otherwise idle)
+    T = 8
+    for M0 in (0.5, 1.0, 1.5, 1.9, 2.0, 2.1, 2.5):
+        tl = timeline.simulate([1.0, 1.0, 1.0], [M0, 0.05, 0.05], T)
+        if M0 <= 2.0:
+            assert tl.stall == 0.0, M0
+        else:
+            assert tl.stall == pytest.approx(T * (M0 - 2.0)), M0
+    # the same M_0 = 1.5 with two tasks stalls every iteration
+    assert timeline.simulate([1.0, 1.0], [1.5, 0.05], T).stall > 0.0
+
+
 def test_speedup_tends_to_one_plus_comm_over_comp():
     C, M, T = [10.0, 10.0], [1.5, 1.5], 400
     tl = timeline.simulate(C, M, T)
