@@ -202,3 +202,8 @@ def make_flat(n: int, std: float, seed: int, dtype=torch.float32, device="cpu") 
     """One flat seeded normal vector (for bucket-level tests that skip the tensor list)."""
     g = _gen(device, seed)
     return (torch.randn(n, generator=g, device=device, dtype=torch.float32) * std).to(dtype)
+
+
+def fill_normal_(t: torch.Tensor, std: float, seed: int) -> torch.Tensor:
+    """Seeded N(0, std) values written in place (no temporaries: for very large buffers)."""
+    return t.normal_(0.0, std, generator=_gen(t.device, seed))
