@@ -161,17 +161,20 @@ def time_param_groups(tasks, stream, reps=30, warm=6):
 
 
 def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False, standin="gemm",
-                   cross_only=False):
+                   cross_only=False, computes=None, label=None, streams=None):
     """Two tasks alternate as in Algorithm 1: one computes (a stand-in for forward + backward)
     while the other synchronises on the second stream.
 
     standin="gemm": the configured chain of bf16 GEMMs.  standin="alu": one arithmetic-only
     kernel of ordinary occupancy and no memory traffic (xs_standin_alu) of the same duration -
-    the kind of kernel a synchronisation wave can share a compute unit with."""
+    the kind of kernel a synchronisation wave can share a compute unit with.
+    computes=(fn_a, fn_b): each task's own computation instead of a stand-in."""
     import torch
     from paper_2103_07974_amd import xs
     g = torch.Generator(device="cuda"); g.manual_seed(task_a.workload.seed + 100)
-    if standin == "gemm":
+    if computes is not None:
+        pass
+    elif standin == "gemm":
         B = (torch.randn(dim, dim, generator=g, device="cuda") / dim ** 0.5).to(torch.bfloat16)
         Y = [torch.randn(dim, dim, generator=g, device="cuda").to(torch.bfloat16) for _ in range(2)]
 
@@ -195,9 +198,11 @@ def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False,
         def compute(stream_ptr):
             xs.standin_alu(256, iters, sink, stream_ptr)
         label = f"one arithmetic-only kernel, 256x256 lanes, {iters} x 8 multiply-adds per lane"
-    apps = [task_a.make_app(compute, fused_gather=fused_gather),
-            task_b.make_app(compute, fused_gather=fused_gather)]
-    cs, ss = torch.cuda.Stream(), torch.cuda.Stream()
+    if computes is None:
+        computes = (compute, compute)
+    apps = [task_a.make_app(computes[0], fused_gather=fused_gather),
+            task_b.make_app(computes[1], fused_gather=fused_gather)]
+    cs, ss = streams if streams is not None else (torch.cuda.Stream(), torch.cuda.Stream())
 
     def run_cross(record=None):
         # Algorithm 1, N = 2, T outer iterations: the first inner step has nothing to
@@ -222,7 +227,7 @@ def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False,
         t0 = time.perf_counter()
         for t in range(T):
             for i in (0, 1):
-                compute(cs.cuda_stream)
+                computes[i](cs.cuda_stream)
                 apps[i].sync(cs)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3
@@ -231,7 +236,7 @@ def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False,
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for t in range(2 * T):
-            compute(cs.cuda_stream)
+            computes[t % 2](cs.cuda_stream)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3
 
@@ -266,7 +271,7 @@ def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False,
             exposed[who] += d; late[who] += 1
     res = {
         "T": T, "compute_standin": label,
-        "sync_kernels": "gather+reduce+SGD+views (1 kernel)" if fused_gather else "8 packs, reduce+SGD, unpack",
+        "sync_kernels": "gather+reduce+SGD+views (1 kernel)" if fused_gather else "W packs (1 launch), reduce+SGD, unpack",
         "t_comp_ms": t_comp, "t_serial_ms": t_serial, "t_cross_ms": t_cross,
         "sum_sync_ms": sum_sync, "sync_a_alone_ms": sync_a, "sync_b_alone_ms": sync_b,
         "compute_chain_ms": t_comp / (2 * T),
@@ -446,6 +451,18 @@ def main():
         extra["crossover_gather_form"] = crossover_pair(ta, tb, fused_gather=True)
         extra["crossover_alu_standin_gather_form"] = crossover_pair(ta, tb, fused_gather=True, standin="alu")
         del ta, tb
+        torch.cuda.empty_cache()
+
+        # a real forward + backward (autograd, fp32 MLPs of about 100 M parameters, one
+        # micro-batch per worker) as each task's computation instead of a stand-in
+        ma = harness.make_mlp_task("mlp_6x4096", [4096] * 7, W=4, batch=256, seed=31)
+        mb = harness.make_mlp_task("mlp_8192_wide", [2048, 8192, 8192, 2048], W=4, batch=256, seed=32)
+        lab = "autograd forward+backward of fp32 ReLU MLPs (6x4096^2 / 2048-8192-8192-2048), 4 micro-batches of 256"
+        extra["crossover_autograd_mlp"] = crossover_pair(ma.state, mb.state, T=10, label=lab,
+                                                         computes=(ma.compute, mb.compute))
+        extra["crossover_autograd_mlp_gather_form"] = crossover_pair(
+            ma.state, mb.state, T=10, label=lab, computes=(ma.compute, mb.compute), fused_gather=True)
+        del ma, mb
         torch.cuda.empty_cache()
 
         bert = harness.make_task(wl.BERT_LARGE_F16, "cuda")

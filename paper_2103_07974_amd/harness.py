@@ -92,3 +92,55 @@ def make_task(w: wl.Workload, device="cuda", align: int = DEFAULT_ALIGN,
     torch.cuda.synchronize(dev)
     return TaskState(w, align, offsets, gplan, pplan, grads, grad_tables, buckets, param_tensors,
                      param_table, params, momentum, found_inf, gather_table)
+
+
+# ---------------------------------------------------------------------------------------
+# A real forward + backward as the compute side of a task (Algorithm 1, "Gradient
+# computation"): a ReLU MLP classifier on seeded synthetic data, one micro-batch per worker,
+# run through PyTorch autograd.  The task's per-layer parameter views ARE the model's weights
+# and biases, and worker w's gradients land in task.grads[w], so the library's kernels read
+# and write the model directly.
+# ---------------------------------------------------------------------------------------
+@dataclass
+class MlpTask:
+    state: TaskState
+    dims: List[int]
+    inputs: List[torch.Tensor]      # [W] micro-batches
+    targets: List[torch.Tensor]     # [W] class labels
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        p = self.state.param_tensors
+        n_layers = len(self.dims) - 1
+        for l in range(n_layers):
+            x = torch.nn.functional.linear(x, p[2 * l].view(self.dims[l + 1], self.dims[l]), p[2 * l + 1])
+            if l + 1 < n_layers:
+                x = torch.relu(x)
+        return x
+
+    def compute(self, stream_ptr: int) -> None:
+        """Forward + backward of every worker's micro-batch, enqueued on the given stream."""
+        s = torch.cuda.ExternalStream(stream_ptr) if stream_ptr else torch.cuda.current_stream()
+        params = self.state.param_tensors
+        with torch.cuda.stream(s):
+            for w in range(self.state.workload.W):
+                loss = torch.nn.functional.cross_entropy(self.forward(self.inputs[w]), self.targets[w])
+                gs = torch.autograd.grad(loss, params)
+                torch._foreach_copy_(self.state.grads[w], list(gs))
+
+
+def make_mlp_task(name: str, dims: List[int], W: int, batch: int, device="cuda", seed: int = 1234,
+                  lr: float = 0.05, momentum: float = 0.9, weight_decay: float = 1e-4,
+                  align: int = DEFAULT_ALIGN) -> MlpTask:
+    shapes = []
+    for l in range(len(dims) - 1):
+        shapes += [(dims[l + 1], dims[l]), (dims[l + 1],)]
+    w = wl.Workload(name=name, shapes=tuple(shapes), W=W, grad_dtype="f32", grad_std=1e-3,
+                    param_std=1.0 / max(dims) ** 0.5, lr=lr, momentum=momentum,
+                    weight_decay=weight_decay, seed=seed)
+    state = make_task(w, device, align)
+    for p in state.param_tensors:
+        p.requires_grad_(True)
+    g = torch.Generator(device=device); g.manual_seed(seed + 5)
+    inputs = [torch.randn(batch, dims[0], generator=g, device=device) for _ in range(W)]
+    targets = [torch.randint(0, dims[-1], (batch,), generator=g, device=device) for _ in range(W)]
+    return MlpTask(state, list(dims), inputs, targets)
