@@ -404,7 +404,7 @@ def main():
                    "W": w.W, "n_elems": w.n_elems, "n_tensors": w.n_tensors,
                    "bucket_align_elems": tasks[0].align,
                    "bytes_per_step_counted": reduce_bytes},
-        "roofline": {"bound": "hbm", "kernel": "xs::reduce_sgd_kernel<8, 0, false, true, true>",
+        "roofline": {"bound": "hbm", "kernel": "xs::reduce_sgd_kernel<8, 0, false, true, true, false>",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
                      "bytes_per_launch": reduce_bytes, "avg_launch_ms": k_avg,
