@@ -71,6 +71,8 @@ struct xs_plan {
     xs::PlanTables tables;
 };
 
+static_assert(sizeof(xs_tensor_hparams) == 16, "the kernels read per-tensor records as 16-byte vectors");
+
 constexpr uint32_t XS_PLAN_MAGIC = 0x78735031u;  // "xsP1"
 constexpr uint32_t XS_APP_MAGIC = 0x78734131u;   // "xsA1"
 

@@ -1,0 +1,180 @@
+"""Seeded random tensor lists through every form of the path, against the oracle.
+
+Each case draws the number of tensors, their sizes (empty, below a vector, around the row
+and chunk sizes, tens of thousands of elements), the bucket alignment (tight layouts
+included), the gradient type, the number of workers, odd tensor base addresses and one
+(lr, momentum, weight decay) record per tensor, then checks
+
+  pack            bit-exact against the oracle's pack, guard zones intact
+  reduce + SGD    0 ulp against the oracle's single-precision evaluation (per-tensor form)
+                  and the fp32 bar against its double-precision definition
+  gathering form  bit-identical to the bucket form, views included
+  unpack          bit-exact against the oracle's unpack
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2103_07974_amd import xs
+
+pytestmark = pytest.mark.gpu
+
+GUARD = 8
+RTOL32, ATOL32 = 1e-6, 1e-7
+TORCH_DT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def _draw_case(seed):
+    rng = np.random.default_rng(9000 + seed)
+    T = int(rng.integers(1, 40))
+    kinds = rng.integers(0, 6, size=T)
+    sizes = []
+    for k in kinds:
+        if k == 0:
+            sizes.append(int(rng.integers(0, 4)))
+        elif k == 1:
+            sizes.append(int(rng.integers(4, 70)))
+        elif k == 2:
+            sizes.append(int(rng.choice([255, 256, 257, 511, 512, 513, 1023, 1024, 1025])))
+        elif k == 3:
+            sizes.append(int(rng.choice([4095, 4096, 4097, 8191, 8192, 8193])))
+        elif k == 4:
+            sizes.append(int(rng.integers(1000, 20000)))
+        else:
+            sizes.append(int(rng.integers(20000, 120000)))
+    return {
+        "rng": rng, "numel": sizes,
+        "align": int(rng.choice([1, 2, 3, 4, 5, 8, 16, 64])),
+        "dtype": str(rng.choice(["f32", "f16", "bf16"])),
+        "W": int(rng.choice([1, 2, 3, 4, 5, 8, 16])),
+        "skew": bool(rng.integers(0, 2)),
+        "triples": [tuple(float(np.float32(v)) for v in
+                          (rng.choice([0.0, 0.05, 0.1, 0.3]), rng.choice([0.0, 0.5, 0.9]),
+                           rng.choice([0.0, 1e-4, 1e-2]))) for _ in sizes],
+        "inv": float(np.float32(rng.choice([1.0, 1.0 / 128, 1.0 / 1024]))),
+    }
+
+
+def _host_grads(rng, n, dtype, std):
+    g = (rng.standard_normal(n) * std).astype(np.float32)
+    if dtype == "f32":
+        return g
+    if dtype == "f16":
+        return g.astype(np.float16)
+    return torch.from_numpy(g).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def _to_device(h, dtype, skew, idx):
+    """A tensor inside its own allocation, at an odd element offset when skew is set,
+    with canary-filled guard elements on both sides."""
+    tdt = TORCH_DT[dtype]
+    sk = (1 + idx % 5) if skew else 0
+    buf = torch.full((h.size + 2 * GUARD + sk,), 7.0, dtype=tdt, device="cuda")
+    v = buf[GUARD + sk:GUARD + sk + h.size]
+    if dtype == "bf16":
+        v.copy_(torch.from_numpy(h.view(np.int16).copy()).view(tdt))
+    else:
+        v.copy_(torch.from_numpy(h.copy()))
+    return buf, v
+
+
+def _np(t):
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def _bits(a):
+    return a.view(np.uint32 if a.dtype.itemsize == 4 else np.uint16)
+
+
+def _ulp_distance(a, b):
+    ia = a.view(np.int32).astype(np.int64); ib = b.view(np.int32).astype(np.int64)
+    ia = np.where(ia < 0, np.int64(-2 ** 31) - ia, ia)
+    ib = np.where(ib < 0, np.int64(-2 ** 31) - ib, ib)
+    return int(np.abs(ia - ib).max()) if a.size else 0
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_list_every_form(seed):
+    c = _draw_case(seed)
+    rng, numel, align, dtype, W = c["rng"], c["numel"], c["align"], c["dtype"], c["W"]
+    print(f"case seed={seed} T={len(numel)} align={align} dtype={dtype} W={W} skew={c['skew']} "
+          f"elems={sum(numel)}", flush=True)
+    offs = xs.bucket_layout(numel, align)
+    offs_np = np.asarray(offs, dtype=np.uint64)
+    assert offs == [int(v) for v in oracle.layout(numel, align)]
+    n_bucket = offs[-1]
+    gplan = xs.Plan(numel, offs, TORCH_DT[dtype])
+    pplan = xs.Plan(numel, offs, torch.float32)
+    std = 1e-3 / c["inv"]          # stored gradients are loss-scaled; unscaled they are ~ 1e-3
+    host_g = [[_host_grads(rng, n, dtype, std) for n in numel] for _ in range(W)]
+    host_p = [(rng.standard_normal(n) * 0.05).astype(np.float32) for n in numel]
+    dev_g = [[_to_device(h, dtype, c["skew"], i) for i, h in enumerate(gl)] for gl in host_g]
+    dev_p = [_to_device(h, "f32", c["skew"], i + 1) for i, h in enumerate(host_p)]
+
+    # ---- pack (all workers in one launch) into guarded buckets
+    want_buckets = [oracle.pack(gl, offs_np) for gl in host_g]
+    raws = [torch.full((n_bucket + 2 * GUARD,), 3.0, dtype=TORCH_DT[dtype], device="cuda")
+            for _ in range(W)]
+    buckets = [r[GUARD:GUARD + n_bucket] for r in raws]
+    tabs = [xs.pointer_table([v for _, v in gl]) if numel else torch.zeros(1, dtype=torch.int64, device="cuda")
+            for gl in dev_g]
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    xs.fuse_pack_many(gplan, tabs, buckets, flag)
+    torch.cuda.synchronize()
+    assert flag.item() == 0
+    for w in range(W):
+        assert np.array_equal(_bits(_np(buckets[w])), _bits(want_buckets[w])), w
+        edge = raws[w].float().cpu().numpy()
+        assert np.all(edge[:GUARD] == 3.0) and np.all(edge[GUARD + n_bucket:] == 3.0)
+    if n_bucket == 0:
+        return
+
+    # ---- state: parameters through the library's own pack, momentum random incl. padding
+    ptab = xs.pointer_table([v for _, v in dev_p])
+    x0 = torch.full((n_bucket,), 9.0, dtype=torch.float32, device="cuda")
+    xs.fuse_pack(pplan, ptab, x0)
+    v0 = torch.from_numpy((rng.standard_normal(n_bucket) * 0.01).astype(np.float32)).cuda()
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(x0.cpu().numpy()), _bits(oracle.pack(host_p, offs_np)))
+
+    # ---- bucket form with per-tensor records vs the oracle
+    table = xs.tensor_hparams_table(c["triples"])
+    x32 = x0.cpu().numpy().copy(); v32 = v0.cpu().numpy().copy()
+    x64 = x32.astype(np.float64); v64 = v32.astype(np.float64)
+    oracle.reduce_sgd_per_tensor(want_buckets, x32, v32, offs_np, c["triples"], c["inv"])
+    oracle.reduce_sgd_per_tensor(want_buckets, x64, v64, offs_np, c["triples"], c["inv"])
+    xb, vb = x0.clone(), v0.clone()
+    xs.fused_reduce_sgd_pt(gplan, buckets, xb, vb, table, c["inv"])
+    torch.cuda.synchronize()
+    gx, gv = xb.cpu().numpy(), vb.cpu().numpy()
+    assert _ulp_distance(gx, x32) == 0 and _ulp_distance(gv, v32) == 0
+    assert np.all(np.abs(gx - x64) <= ATOL32 + RTOL32 * np.abs(x64))
+    assert np.all(np.abs(gv - v64) <= ATOL32 + RTOL32 * np.abs(v64))
+
+    # ---- gathering form, in place, views at odd addresses
+    views = [_to_device(np.zeros(n, np.float32), "f32", c["skew"], i + 2) for i, n in enumerate(numel)]
+    vtab = xs.pointer_table([v for _, v in views])
+    gtab = xs.gather_pointer_table([[v for _, v in gl] for gl in dev_g])
+    xg, vg = x0.clone(), v0.clone()
+    xs.fused_gather_reduce_sgd_pt(gplan, gtab, W, xg, vg, table, c["inv"], param_tensor_ptrs=vtab)
+    torch.cuda.synchronize()
+    assert torch.equal(xg, xb) and torch.equal(vg, vb)
+    want_views = oracle.unpack(x32, numel, offs_np)
+    for t, ((hold, v), want) in enumerate(zip(views, want_views)):
+        assert np.array_equal(_bits(v.cpu().numpy()), _bits(want)), t
+        h = hold.cpu().numpy()
+        lo = h.size - numel[t] - GUARD
+        assert np.all(h[:lo] == 7.0) and np.all(h[lo + numel[t]:] == 7.0), t
+
+    # ---- unpack of the bucket-form result
+    outs = [_to_device(np.zeros(n, np.float32), "f32", c["skew"], i + 3) for i, n in enumerate(numel)]
+    xs.fuse_unpack(pplan, xb, xs.pointer_table([v for _, v in outs]))
+    torch.cuda.synchronize()
+    for t, ((hold, v), want) in enumerate(zip(outs, want_views)):
+        assert np.array_equal(_bits(v.cpu().numpy()), _bits(want)), t
+        h = hold.cpu().numpy()
+        lo = h.size - numel[t] - GUARD
+        assert np.all(h[:lo] == 7.0) and np.all(h[lo + numel[t]:] == 7.0), t
