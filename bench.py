@@ -430,7 +430,33 @@ def main():
             torch.cuda.synchronize()
             tk["step_latency_us"] = (time.perf_counter() - t0) * 1e6 / 200
         app.destroy()
-        extra["tiny_mlp"] = {k: tk[k] for k in ("pack_ms", "reduce_sgd_ms", "unpack_ms", "step_latency_us")}
+        # the same step as one gathering kernel, eager and replayed from a captured HIP graph
+        app = tiny.make_app(fused_gather=True)
+        with torch.cuda.stream(stream):
+            for _ in range(20):
+                app.sync(stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(200):
+                app.sync(stream)
+            torch.cuda.synchronize()
+            tk["gather_step_latency_us"] = (time.perf_counter() - t0) * 1e6 / 200
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for _ in range(10):
+                app.sync(stream)
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            graph.replay()
+        torch.cuda.synchronize()
+        tk["gather_step_latency_graph_us"] = (time.perf_counter() - t0) * 1e6 / 200
+        del graph
+        app.destroy()
+        extra["tiny_mlp"] = {k: tk[k] for k in ("pack_ms", "reduce_sgd_ms", "unpack_ms", "step_latency_us",
+                                                "gather_step_latency_us", "gather_step_latency_graph_us")}
 
         ta = harness.make_task(wl.RESNET50, "cuda")
         tb = harness.make_task(wl.VGG16, "cuda")
