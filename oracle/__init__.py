@@ -235,7 +235,7 @@ def round_params(x: np.ndarray, dtype_code: int) -> np.ndarray:
 def sync_step(grads: Sequence[Sequence[np.ndarray]], params: Sequence[np.ndarray],
               v_bucket: np.ndarray, lr: float, mu: float, wd: float,
               inv_loss_scale: float = 1.0, align: int = 1, precision: str = "f64",
-              tensor_hp: Sequence[Sequence[float]] | None = None):
+              tensor_hp: Sequence[Sequence[float]] | None = None, threads: int = 1):
     """One whole synchronisation of one task: pack every worker's tensor list, test
     for overflow, average + update, unpack the new parameters.
 
@@ -243,7 +243,8 @@ def sync_step(grads: Sequence[Sequence[np.ndarray]], params: Sequence[np.ndarray
     v_bucket: momentum in bucket layout (float64 for "f64", float32 for "f32"),
     updated in place.  Returns (new_params list in the working precision, found_inf).
     A skipped step returns the parameters unchanged.  tensor_hp, if given, replaces
-    (lr, mu, wd) by one triple per tensor.
+    (lr, mu, wd) by one triple per tensor.  threads > 1 runs the element loop of the
+    average + update under OpenMP (elements are independent; results do not change).
     """
     numel = [p.size for p in params]
     offs = layout(numel, align)
@@ -255,7 +256,7 @@ def sync_step(grads: Sequence[Sequence[np.ndarray]], params: Sequence[np.ndarray
     if tensor_hp is not None:
         reduce_sgd_per_tensor(buckets, x, v_bucket, offs, tensor_hp, inv_loss_scale)
     elif precision == "f64":
-        reduce_sgd_f64(buckets, x, v_bucket, lr, mu, wd, inv_loss_scale)
+        reduce_sgd_f64(buckets, x, v_bucket, lr, mu, wd, inv_loss_scale, threads)
     else:
-        reduce_sgd_f32(buckets, x, v_bucket, lr, mu, wd, inv_loss_scale)
+        reduce_sgd_f32(buckets, x, v_bucket, lr, mu, wd, inv_loss_scale, threads)
     return unpack(x, numel, offs), False

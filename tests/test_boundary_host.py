@@ -153,3 +153,31 @@ def test_mixed_precision_option_validation():
     assert reduce_mp(FAKE + 0x5002, xs.XS_F16) == xs.XS_ERR_ALIGNMENT
     assert reduce_mp(FAKE + 0x1000, xs.XS_BF16) == xs.XS_ERR_INVALID_ARG     # on top of momentum
     assert reduce_mp(FAKE + 0x20010, xs.XS_F16) == xs.XS_ERR_INVALID_ARG     # on top of a replica
+
+
+def test_per_tensor_and_n_task_entry_points_reject_bad_handles():
+    L = xs.lib()
+    arr = (ctypes.c_void_p * 2)(FAKE + 0x20000, FAKE + 0x30000)
+    junk = ctypes.create_string_buffer(256)
+    for plan in (None, ctypes.addressof(junk)):
+        assert L.xs_fused_reduce_sgd_pt(plan, arr, 2, FAKE, FAKE + 0x1000, None, None, FAKE + 0x8000,
+                                        1.0, None, None, None) == xs.XS_ERR_INVALID_ARG
+        assert L.xs_fused_gather_reduce_sgd_pt(plan, FAKE, 2, FAKE, FAKE + 0x1000, None, None, None,
+                                               FAKE + 0x8000, 1.0, None, None, None) == xs.XS_ERR_INVALID_ARG
+    assert "plan" in xs.last_error()
+    # N-task loop: an empty array is a no-op, anything else must be apps
+    assert L.xs_crossover_iteration(None, 0, None, None) == xs.XS_OK
+    assert L.xs_crossover_finish(None, 0, None) == xs.XS_OK
+    assert L.xs_crossover_iteration(None, 2, None, None) == xs.XS_ERR_INVALID_ARG
+    assert L.xs_crossover_finish(None, 2, None) == xs.XS_ERR_INVALID_ARG
+    apps = (ctypes.c_void_p * 2)(ctypes.addressof(junk), None)
+    assert L.xs_crossover_iteration(apps, 2, None, None) == xs.XS_ERR_INVALID_ARG
+    assert L.xs_crossover_finish(apps, 2, None) == xs.XS_ERR_INVALID_ARG
+    assert "apps[0]" in xs.last_error()
+
+
+def test_header_record_is_sixteen_bytes_of_floats():
+    # the binding builds the per-tensor table as rows of four float32
+    text = open(HEADER).read()
+    start = text.index("typedef struct {\n    float lr;\n    float momentum;\n    float weight_decay;\n    float reserved;")
+    assert "} xs_tensor_hparams;" in text[start:start + 300]

@@ -316,3 +316,21 @@ def test_round_params_matches_library_conversions():
     want_b = _bf16_bits(torch.from_numpy(x.copy()))
     assert np.array_equal(b[~nan], want_b[~nan])
     assert np.all((b[nan] & 0x7f80) == 0x7f80) and np.all((b[nan] & 0x007f) != 0)
+
+
+def test_threads_do_not_change_the_result():
+    # elements are independent: spreading the element loop over threads is bit-neutral
+    rng = np.random.default_rng(77)
+    numel = [1000, 3, 5000]
+    grads = [[rng.standard_normal(n).astype(np.float32) for n in numel] for _ in range(4)]
+    params = [rng.standard_normal(n).astype(np.float32) for n in numel]
+    for prec, dt in (("f64", np.float64), ("f32", np.float32)):
+        outs = []
+        for threads in (1, 4):
+            v = np.zeros(int(oracle.layout(numel, 8)[-1]), dt)
+            new, inf = oracle.sync_step(grads, params, v, 0.1, 0.9, 1e-4, 0.5, align=8,
+                                        precision=prec, threads=threads)
+            outs.append((new, v))
+        for a, b in zip(outs[0][0], outs[1][0]):
+            assert np.array_equal(a, b)
+        assert np.array_equal(outs[0][1], outs[1][1])
