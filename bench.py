@@ -160,6 +160,39 @@ def time_param_groups(tasks, stream, reps=30, warm=6):
     return out
 
 
+def time_overflow_skip(task, stream, reps=8):
+    """Loss-scale overflow (the mixed-precision workload with non-finite gradients in one
+    replica): the W packs with detection raise the flag, the reduce + SGD launched behind them
+    returns at once and leaves the state untouched."""
+    import torch
+    from paper_2103_07974_amd import xs
+    w = task.workload
+    g = torch.Generator(device="cuda"); g.manual_seed(w.seed + 999)
+    for t in task.grads[0]:           # about 0.1 % of replica 0's elements become +inf
+        k = max(1, t.numel() // 1000)
+        idx = torch.randint(0, t.numel(), (k,), generator=g, device="cuda")
+        t.view(-1)[idx] = float("inf")
+    x_before = task.params[:4096].clone()
+    pack_ms, red_ms = [], []
+    with torch.cuda.stream(stream):
+        for i in range(reps + 2):
+            task.found_inf.zero_()
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record(stream)
+            xs.fuse_pack_many(task.gplan, task.grad_tables, task.buckets, task.found_inf, stream)
+            e[1].record(stream)
+            xs.fused_reduce_sgd(task.buckets, task.n_bucket, task.params, task.momentum, w.lr,
+                                w.momentum, w.weight_decay, 1.0 / w.loss_scale,
+                                found_inf=task.found_inf, stream=stream)
+            e[2].record(stream); e[2].synchronize()
+            if i >= 2:
+                pack_ms.append(e[0].elapsed_time(e[1])); red_ms.append(e[1].elapsed_time(e[2]))
+    assert int(task.found_inf.item()) == 1 and torch.equal(task.params[:4096], x_before)
+    return {"pack_all_replicas_with_detection_ms": _median(pack_ms),
+            "pack_all_replicas_with_detection_GBs": w.W * task.pack_bytes() / _median(pack_ms) / 1e6,
+            "skipped_reduce_sgd_ms": _median(red_ms), "flag_raised": True}
+
+
 def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False, standin="gemm",
                    cross_only=False, computes=None, label=None, streams=None):
     """Two tasks alternate as in Algorithm 1: one computes (a stand-in for forward + backward)
@@ -509,6 +542,7 @@ def main():
         extra["bert_large_f16"] = time_kernels(bert, stream, reps=15, warm=3)
         extra["bert_large_f16"]["gather_form"] = time_gather([bert], stream, reps=10, warm=2)
         extra["bert_large_f16"]["param_groups"] = time_param_groups([bert], stream, reps=10, warm=2)
+        extra["bert_large_f16"]["overflow_skip"] = time_overflow_skip(bert, stream)
         del bert
         torch.cuda.empty_cache()
 
