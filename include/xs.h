@@ -290,7 +290,9 @@ int xs_app_sync(xs_app *app, void *hip_stream);
  * it sees updated parameters) while sync_app's synchronisation is enqueued on
  * sync_stream (after the computation that produced its gradients).  sync_app ==
  * NULL is the first-iteration bypass of Section 2.2.  Returns XS_ERR_STATE if
- * sync_app has no gradients outstanding.  Enqueue only; no host synchronisation.
+ * sync_app has no gradients outstanding, or if compute_app still has: its gradient
+ * tensors would be overwritten before they were synchronised.  Enqueue only; no host
+ * synchronisation.
  */
 int xs_crossover_step(xs_app *compute_app, xs_app *sync_app,
                       void *compute_stream, void *sync_stream);

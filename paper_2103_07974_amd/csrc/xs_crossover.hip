@@ -189,6 +189,9 @@ extern "C" int xs_crossover_step(xs_app *x, xs_app *y, void *compute_stream, voi
     if (!is_app(x)) return fail(XS_ERR_INVALID_ARG, "xs_crossover_step: compute_app is NULL or not an app");
     if (y && !is_app(y)) return fail(XS_ERR_INVALID_ARG, "xs_crossover_step: sync_app is not an app");
     hipStream_t cs = (hipStream_t)compute_stream, ss = (hipStream_t)sync_stream;
+    if (x->grads_outstanding)
+        return fail(XS_ERR_STATE, "xs_crossover_step: compute_app's previous gradients have not been "
+                                  "synchronised; computing again would overwrite them");
     if (y == x) {
         // a single task degenerates to compute, then synchronise, in order
         int rc = compute_on_stream(x, cs);

@@ -172,6 +172,9 @@ def test_out_of_order_calls_are_refused():
         xs.crossover_drain(apps[0], ss)
     assert e.value.status == xs.XS_ERR_STATE
     xs.crossover_step(apps[0], None, cs, ss)                  # first-iteration bypass
+    with pytest.raises(xs.XsError) as e:
+        xs.crossover_step(apps[0], None, cs, ss)              # a's gradients would be overwritten
+    assert e.value.status == xs.XS_ERR_STATE
     xs.crossover_step(apps[1], apps[0], cs, ss)
     with pytest.raises(xs.XsError):
         xs.crossover_drain(apps[0], ss)                       # already synchronised
