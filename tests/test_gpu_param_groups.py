@@ -65,12 +65,13 @@ def _random_state(task, seed):
     return x, v
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
-@pytest.mark.parametrize("align", [1, 4, 64])
-@pytest.mark.parametrize("W", [1, 2, 3, 8, 16])
+# bf16 shares every code path with f16 but the widening, so it runs a subset of the grid
+CASES = [(d, a, W) for d in ("f32", "f16", "bf16") for a in (1, 4, 64) for W in (1, 2, 3, 8, 16)
+         if not (d == "bf16" and (a == 4 or W in (1, 3)))]
+
+
+@pytest.mark.parametrize("dtype,align,W", CASES)
 def test_bucket_and_gather_forms_match_oracle(dtype, align, W):
-    if dtype == "bf16" and (align == 4 or W in (1, 3)):
-        pytest.skip("bf16 shares every code path with f16 but the widening; a subset suffices")
     base = wl.RESNET50 if dtype == "f32" else wl.BERT_LARGE_F16
     w = wl.scaled(base, f"pt_{dtype}", [(n,) for n in SIZES], W=W, grad_dtype=dtype)
     print(f"case dtype={dtype} align={align} W={W}", flush=True)
