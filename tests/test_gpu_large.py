@@ -35,6 +35,7 @@ def _ulp_distance(a, b):
 
 
 def test_bucket_of_more_than_2_to_32_elements():
+    torch.cuda.empty_cache()          # hand cached blocks of earlier tests back first
     free, _ = torch.cuda.mem_get_info()
     if free < 200 * 2 ** 30:
         pytest.skip("needs about 160 GiB of device memory")
@@ -114,3 +115,5 @@ def test_bucket_of_more_than_2_to_32_elements():
     torch.cuda.synchronize()
     for t, n in enumerate(NUMEL):
         assert torch.equal(views[t], xb[offs[t]:offs[t] + n]), t
+    del grads, buckets, x0, v0, xb, vb, xg, vg, views
+    torch.cuda.empty_cache()
