@@ -522,6 +522,7 @@ def main():
         extra["vgg16"]["gather_form"] = time_gather([tb], stream, reps=15, warm=3)
         extra["crossover"] = crossover_pair(ta, tb)
         extra["crossover_gather_form"] = crossover_pair(ta, tb, fused_gather=True)
+        extra["crossover_alu_standin"] = crossover_pair(ta, tb, standin="alu")
         extra["crossover_alu_standin_gather_form"] = crossover_pair(ta, tb, fused_gather=True, standin="alu")
         del ta, tb
         torch.cuda.empty_cache()

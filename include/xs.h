@@ -52,7 +52,8 @@ typedef enum {
     XS_ERR_UNSUPPORTED = -4,  /* unknown dtype or option */
     XS_ERR_HIP         = -5,  /* a HIP runtime call failed; see xs_last_error() */
     XS_ERR_NOMEM       = -6,  /* host or device allocation failed in a *_create call */
-    XS_ERR_STATE       = -7   /* crossover call out of order (nothing to synchronise) */
+    XS_ERR_STATE       = -7   /* crossover call out of order (nothing to synchronise, or
+                                 gradients that would be overwritten) */
 } xs_status;
 
 typedef enum { XS_F32 = 0, XS_F16 = 1, XS_BF16 = 2 } xs_dtype;   /* element types */
@@ -335,7 +336,9 @@ int xs_standin_alu(uint32_t workgroups, uint32_t iters, float *sink, void *hip_s
 typedef enum {
     XS_TUNE_REDUCE_WG_PER_CU = 0,   /* reduce kernels: workgroups per compute unit for a grid-stride
                                        launch; 0 (default) = one 16-byte vector per lane, no loop */
-    XS_TUNE_COPY_WG_PER_CU = 1,     /* pack/unpack: workgroups per compute unit (default 16) */
+    XS_TUNE_COPY_WG_PER_CU = 1,     /* pack/unpack: workgroups per compute unit of a persistent grid;
+                                       0 (default) = one 16 KiB chunk per workgroup, dispatched in
+                                       bucket order (a few chunks when the tensor table is large) */
     XS_TUNE_NT_GRADS = 2,           /* bucket-form reduce: non-temporal gradient loads (0/1, default 1) */
     XS_TUNE_NT_STATE = 3,           /* bucket-form reduce: non-temporal parameter/momentum accesses (0/1, default 1) */
     XS_TUNE_REDUCE_LDS_RESERVE = 4, /* bytes of LDS reserved per reduce workgroup; the kernel uses no
@@ -345,7 +348,10 @@ typedef enum {
     XS_TUNE_COPY_MAX_WG = 6,        /*   synchronisation that runs beside another task's computation */
     XS_TUNE_COPY_NT = 7,            /* pack/unpack: non-temporal accesses (0/1, default 1) */
     XS_TUNE_GATHER_LDS_RESERVE = 8, /* as 4 for the gathering form; -1 = 8192 fp32, 16384 half */
-    XS_TUNE_COUNT = 9
+    XS_TUNE_COPY_LDS_RESERVE = 9,   /* pack/unpack: bytes of LDS reserved per 256-lane workgroup beyond its
+                                       tensor table (caps the workgroups per compute unit so that another
+                                       task's kernels can still be placed beside them); -1 (default) = 32768 */
+    XS_TUNE_COUNT = 10
 } xs_tuning_key;
 int xs_tuning_set(int key, int value);
 int xs_tuning_get(int key, int *value_out);

@@ -43,9 +43,9 @@ int compute_units()
 }
 
 // -1 = chosen per gradient dtype at launch (see launch_reduce_sgd)
-Tuning g_tuning = {/*reduce_wg_per_cu*/ 0, /*copy_wg_per_cu*/ 16, /*nt_grads*/ 1, /*nt_state*/ 1,
+Tuning g_tuning = {/*reduce_wg_per_cu*/ 0, /*copy_wg_per_cu*/ 0, /*nt_grads*/ 1, /*nt_state*/ 1,
                    /*reduce_lds_reserve*/ -1, /*reduce_max_wg*/ 0, /*copy_max_wg*/ 0,
-                   /*copy_nt*/ 1, /*gather_lds_reserve*/ -1};
+                   /*copy_nt*/ 1, /*gather_lds_reserve*/ -1, /*copy_lds_reserve*/ -1};
 
 }  // namespace xs
 
@@ -75,7 +75,7 @@ struct TuningSlot {
 };
 const TuningSlot kTuning[XS_TUNE_COUNT] = {
     {&xs::Tuning::reduce_wg_per_cu, 0, 64},       // XS_TUNE_REDUCE_WG_PER_CU
-    {&xs::Tuning::copy_wg_per_cu, 1, 64},         // XS_TUNE_COPY_WG_PER_CU
+    {&xs::Tuning::copy_wg_per_cu, 0, 4096},       // XS_TUNE_COPY_WG_PER_CU
     {&xs::Tuning::nt_grads, 0, 1},                // XS_TUNE_NT_GRADS
     {&xs::Tuning::nt_state, 0, 1},                // XS_TUNE_NT_STATE
     {&xs::Tuning::reduce_lds_reserve, -1, 65536}, // XS_TUNE_REDUCE_LDS_RESERVE
@@ -83,6 +83,7 @@ const TuningSlot kTuning[XS_TUNE_COUNT] = {
     {&xs::Tuning::copy_max_wg, 0, 0x7fffffff},    // XS_TUNE_COPY_MAX_WG
     {&xs::Tuning::copy_nt, 0, 1},                 // XS_TUNE_COPY_NT
     {&xs::Tuning::gather_lds_reserve, -1, 65536}, // XS_TUNE_GATHER_LDS_RESERVE
+    {&xs::Tuning::copy_lds_reserve, -1, 65536},   // XS_TUNE_COPY_LDS_RESERVE
 };
 }  // namespace
 

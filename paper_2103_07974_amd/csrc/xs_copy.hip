@@ -4,10 +4,11 @@
 //
 // One launch moves the whole list, however many small tensors it has.  The bucket
 // is cut into chunks of kChunkBytes of one tensor's segment (tensor + trailing
-// padding); a persistent grid of workgroups walks the chunk ids in stride.  Each
-// workgroup copies the per-tensor chunk-count prefix table into LDS once and finds
-// the tensor of every chunk by binary search there (the table is uniform across
-// the workgroup, so the LDS reads are broadcasts).  Inside a chunk each lane moves
+// padding); by default every workgroup takes one chunk, in bucket order (a persistent
+// grid striding over the chunk ids can be asked for instead).  Each workgroup copies the
+// per-tensor chunk-count prefix table into LDS once and finds the tensor of its chunk by
+// binary search there (the table is uniform across the workgroup, so the LDS reads are
+// broadcasts).  Inside a chunk each lane moves
 // 16-byte vectors: the bucket side is always 16-byte aligned, the tensor side is
 // accessed with element-aligned 16-byte loads/stores (gfx950 global memory
 // instructions do not need natural alignment), so tight layouts and odd tensor
@@ -199,16 +200,34 @@ static int launch_copy(const xs_plan *plan, const void *const *tables, void *con
         pairs.buckets[i] = i < n_pairs ? (unsigned char *)buckets[i] : nullptr;
     }
     const uint64_t n_items = (uint64_t)n_pairs * plan->n_chunks;
-    uint64_t blocks = (uint64_t)cus * (uint64_t)g_tuning.copy_wg_per_cu;
+    const bool lds = plan->n_tensors + 1 <= kLdsPrefixCap;
+    const size_t lds_bytes = lds ? (size_t)(plan->n_tensors + 1) * 4 : 0;
+    // Measured on MI355X: one chunk per workgroup, dispatched in bucket order as earlier
+    // workgroups retire, moves 8-9 % more than a persistent grid of 16 workgroups per compute
+    // unit striding over the chunks (as for the reduce kernels, the DRAM access front stays
+    // tight).  Every workgroup stages the chunk-prefix table in LDS first, so lists with a table
+    // beyond 4 KiB give each workgroup one more chunk per further 4 KiB to amortise that.
+    uint64_t blocks;
+    if (g_tuning.copy_wg_per_cu > 0) {
+        blocks = (uint64_t)cus * (uint64_t)g_tuning.copy_wg_per_cu;
+    } else {
+        const uint64_t per_wg = lds_bytes > 4096 ? (lds_bytes + 4095) / 4096 : 1;
+        blocks = (n_items + per_wg - 1) / per_wg;
+    }
     if (g_tuning.copy_max_wg > 0 && blocks > (uint64_t)g_tuning.copy_max_wg)
         blocks = (uint64_t)g_tuning.copy_max_wg;
     if (blocks > n_items) blocks = n_items;
-    const bool lds = plan->n_tensors + 1 <= kLdsPrefixCap;
-    const size_t lds_bytes = lds ? (size_t)(plan->n_tensors + 1) * 4 : 0;
+    if (blocks > 0x7fffffffull) blocks = 0x7fffffffull;   // the loop covers the rest
     const bool nt = g_tuning.copy_nt != 0;
     const dim3 grid((unsigned)blocks), block(kCopyThreads);
+    // Measured on MI355X: five 256-lane workgroups per compute unit (32 KiB of LDS each, only the
+    // table's share of it used) copy 6 % faster than the eight that fit otherwise, and they leave
+    // wave slots on every compute unit, so that another task's workgroups dispatched meanwhile
+    // spread evenly instead of piling up on the few compute units that happen to have room.
+    const size_t reserve = g_tuning.copy_lds_reserve < 0 ? 32768 : (size_t)g_tuning.copy_lds_reserve;
+    const size_t lds_launch = (lds_bytes > reserve ? lds_bytes : reserve);
 #define XS_COPY_LAUNCH(LDS, NT)                                                                   \
-    hipLaunchKernelGGL((copy_kernel<UNPACK, DETECT, DT, LDS, NT>), grid, block, (LDS) ? lds_bytes : 0, \
+    hipLaunchKernelGGL((copy_kernel<UNPACK, DETECT, DT, LDS, NT>), grid, block, lds_launch,        \
                        stream, plan->tables, plan->n_tensors, plan->n_chunks, n_pairs, pairs, found_inf)
     if (lds) { if (nt) XS_COPY_LAUNCH(true, true); else XS_COPY_LAUNCH(true, false); }
     else     { if (nt) XS_COPY_LAUNCH(false, true); else XS_COPY_LAUNCH(false, false); }

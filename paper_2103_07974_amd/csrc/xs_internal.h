@@ -27,7 +27,7 @@ int compute_units();   // > 0, or a negative xs_status
 // ---- tuning ---------------------------------------------------------------------
 struct Tuning {              // indexed by xs_tuning_key
     int reduce_wg_per_cu;     // 0: one vector per lane, no loop
-    int copy_wg_per_cu;
+    int copy_wg_per_cu;       // 0: one work item per workgroup (a few for large LDS tables)
     int nt_grads;             // non-temporal loads of gradient replicas
     int nt_state;             // non-temporal loads and stores of parameters and momentum
     int reduce_lds_reserve;   // bytes of LDS reserved per reduce workgroup (-1: per dtype)
@@ -35,6 +35,7 @@ struct Tuning {              // indexed by xs_tuning_key
     int copy_max_wg;          // absolute cap on pack/unpack workgroups (0 = none)
     int copy_nt;              // non-temporal loads and stores in pack/unpack
     int gather_lds_reserve;   // as reduce_lds_reserve, for the gathering form
+    int copy_lds_reserve;     // LDS reserved per pack/unpack workgroup beyond its table (-1: default)
 };
 extern Tuning g_tuning;
 

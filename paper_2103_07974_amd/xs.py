@@ -40,7 +40,8 @@ TUNE_REDUCE_MAX_WG = 5
 TUNE_COPY_MAX_WG = 6
 TUNE_COPY_NT = 7
 TUNE_GATHER_LDS_RESERVE = 8
-N_TUNING_KEYS = 9
+TUNE_COPY_LDS_RESERVE = 9
+N_TUNING_KEYS = 10
 
 EXPORTS = [
     "xs_status_string", "xs_last_error", "xs_bucket_layout", "xs_plan_create", "xs_plan_destroy",

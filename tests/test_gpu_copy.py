@@ -190,3 +190,52 @@ def test_pack_many_equals_single_packs(torch_dtype, np_dtype):
     assert int(flag.item()) == 1
     xs.fuse_pack_many(plan, [], [])               # n = 0 is a no-op
     plan.destroy()
+
+
+@pytest.mark.parametrize("wg_per_cu,max_wg", [(0, 0), (1, 0), (16, 0), (4096, 0), (0, 3), (16, 7)])
+def test_launch_shapes_give_identical_copies(wg_per_cu, max_wg):
+    """One chunk per workgroup (default), persistent grids of several sizes and capped grids
+    (more chunks than workgroups: the loop covers the rest) all produce the same bits."""
+    old = [xs.tuning_get(k) for k in range(xs.N_TUNING_KEYS)]
+    try:
+        xs.tuning_set(xs.TUNE_COPY_WG_PER_CU, wg_per_cu)
+        xs.tuning_set(xs.TUNE_COPY_MAX_WG, max_wg)
+        rng = np.random.default_rng(31)
+        numel = [70000, 3, 0, 4097, 64, 200001, 17]
+        offs = xs.bucket_layout(numel, 4)
+        offs_np = np.asarray(offs, dtype=np.uint64)
+        plan = xs.Plan(numel, offs, torch.float32)
+        hosts = [[_random_bits(rng, n, np.float32) for n in numel] for _ in range(3)]
+        devs = [_device_tensors(h, torch.float32, 1) for h in hosts]
+        buckets = [torch.full((offs[-1],), 3.0, device="cuda") for _ in range(3)]
+        xs.fuse_pack_many(plan, [xs.pointer_table(v) for _, v in devs], buckets)
+        torch.cuda.synchronize()
+        for h, b in zip(hosts, buckets):
+            assert np.array_equal(_bits(b.cpu().numpy()), _bits(oracle.pack(h, offs_np)))
+        outs_h, outs = _device_tensors([np.zeros(n, np.float32) for n in numel], torch.float32, 1)
+        xs.fuse_unpack(plan, buckets[1], xs.pointer_table(outs))
+        torch.cuda.synchronize()
+        for h, v in zip(hosts[1], outs):
+            assert np.array_equal(_bits(v.cpu().numpy()), _bits(h))
+        plan.destroy()
+    finally:
+        for k, v in enumerate(old):
+            xs.tuning_set(k, v)
+
+
+def test_large_table_gives_each_workgroup_several_chunks():
+    """A tensor list whose chunk-prefix table is beyond 4 KiB but still fits LDS."""
+    rng = np.random.default_rng(32)
+    numel = [int(n) for n in rng.integers(0, 40, size=5000)] + [100000]
+    offs = xs.bucket_layout(numel, 1)
+    plan = xs.Plan(numel, offs, torch.float16)
+    flat = _random_bits(rng, sum(numel), np.float16)
+    hosts = np.split(flat, np.cumsum(numel)[:-1])
+    dev = torch.from_numpy(flat.copy()).cuda()
+    views = list(torch.split(dev, numel))
+    bucket = torch.full((offs[-1],), 3.0, dtype=torch.float16, device="cuda")
+    xs.fuse_pack(plan, xs.pointer_table(views), bucket)
+    torch.cuda.synchronize()
+    want = oracle.pack([np.ascontiguousarray(h) for h in hosts], np.asarray(offs, dtype=np.uint64))
+    assert np.array_equal(_bits(bucket.cpu().numpy()), _bits(want))
+    plan.destroy()
