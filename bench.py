@@ -408,6 +408,8 @@ def main():
                     help="run only the crossover pair (T outer iterations), for rocprofv3 --kernel-trace")
     ap.add_argument("--T", type=int, default=20)
     ap.add_argument("--gather", action="store_true", help="with --crossover-only: gathering form")
+    ap.add_argument("--autograd", action="store_true",
+                    help="with --crossover-only: the two autograd MLP tasks instead of the GEMM-chain stand-in")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="launch a calibration copy and the path's kernels a few times (for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -424,6 +426,13 @@ def main():
     torch.cuda.set_device(0)
     stream = torch.cuda.Stream()
 
+    if args.crossover_only and args.autograd:
+        ma = harness.make_mlp_task("mlp_6x4096", [4096] * 7, W=4, batch=256, seed=31)
+        mb = harness.make_mlp_task("mlp_8192_wide", [2048, 8192, 8192, 2048], W=4, batch=256, seed=32)
+        print(json.dumps(crossover_pair(ma.state, mb.state, T=args.T, fused_gather=args.gather,
+                                        cross_only=True, computes=(ma.compute, mb.compute),
+                                        label="autograd forward+backward of two fp32 MLPs")))
+        return 0
     if args.crossover_only:
         ta = harness.make_task(wl.RESNET50, "cuda")
         tb = harness.make_task(wl.VGG16, "cuda")
