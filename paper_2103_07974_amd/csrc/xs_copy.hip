@@ -183,8 +183,7 @@ __global__ __launch_bounds__(kCopyThreads) void copy_kernel(
     }
 
     if constexpr (DETECT) {
-        if (__builtin_amdgcn_ballot_w64(bad) != 0ull && (threadIdx.x & 63u) == 0u)
-            atomicOr(found_inf, 1);
+        raise_flag_if(bad, found_inf);
     }
 }
 

@@ -208,6 +208,18 @@ __device__ __forceinline__ void exchange_half_row(float (&s)[8])
     for (int e = 0; e < 8; ++e) s[e] = t[e];
 }
 
+// ---- overflow flag ---------------------------------------------------------------------------
+// Wavefront-level vote, then at most one atomic per wavefront that saw a non-finite value -
+// and none once the flag is up: with many such wavefronts (0.1 % of the elements non-finite
+// puts one in nearly every workgroup) the atomics on the one address would otherwise queue up
+// behind each other in L2.
+__device__ __forceinline__ void raise_flag_if(bool bad, int32_t *found_inf)
+{
+    if (__builtin_amdgcn_ballot_w64(bad) != 0ull && (threadIdx.x & 63u) == 0u) {
+        if (*(volatile int32_t *)found_inf == 0) atomicOr(found_inf, 1);
+    }
+}
+
 // Accumulate one replica's 16-byte gradient vector into the per-lane sums, in worker order.
 template <int GT, bool DETECT>
 __device__ __forceinline__ void accumulate(const u32x4 &g, bool first, float *s, bool &bad)

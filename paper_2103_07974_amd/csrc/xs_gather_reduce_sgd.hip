@@ -201,8 +201,7 @@ __global__ __launch_bounds__(kWave) void gather_reduce_sgd_kernel(GatherArgs a)
     }
 
     if constexpr (DETECT) {
-        if (__builtin_amdgcn_ballot_w64(bad) != 0ull && (threadIdx.x & 63u) == 0u)
-            atomicOr(a.found_inf, 1);
+        raise_flag_if(bad, a.found_inf);
     }
 }
 
@@ -224,8 +223,7 @@ __global__ __launch_bounds__(kWave) void gather_reduce_sgd_anyw_kernel(GatherArg
         }
     }
     if constexpr (DETECT) {
-        if (__builtin_amdgcn_ballot_w64(bad) != 0ull && (threadIdx.x & 63u) == 0u)
-            atomicOr(a.found_inf, 1);
+        raise_flag_if(bad, a.found_inf);
     }
 }
 

@@ -157,9 +157,7 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(ReplicaPtrs<W> rep
         tail_element<GT, DETECT, PT>(reps, (uint32_t)W, a, nvec * VEC + threadIdx.x, bad);
 
     if constexpr (DETECT) {
-        // wavefront-level vote, then at most one atomic per wavefront
-        if (__builtin_amdgcn_ballot_w64(bad) != 0ull && (threadIdx.x & 63u) == 0u)
-            atomicOr(a.found_inf, 1);
+        raise_flag_if(bad, a.found_inf);
     }
 }
 
@@ -200,8 +198,7 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_anyw_kernel(
     if (blockIdx.x == 0 && threadIdx.x < rem)
         tail_element<GT, DETECT, PT>(reps, W, a, nvec * VEC + threadIdx.x, bad);
     if constexpr (DETECT) {
-        if (__builtin_amdgcn_ballot_w64(bad) != 0ull && (threadIdx.x & 63u) == 0u)
-            atomicOr(a.found_inf, 1);
+        raise_flag_if(bad, a.found_inf);
     }
 }
 
