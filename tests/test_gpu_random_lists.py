@@ -96,11 +96,41 @@ def _ulp_distance(a, b):
     return int(np.abs(ia - ib).max()) if a.size else 0
 
 
+def _fixed_case(numel, align, dtype, W, skew, inv=1.0):
+    rng = np.random.default_rng(4242 + len(numel) + align + W)
+    return {"rng": rng, "numel": list(numel), "align": align, "dtype": dtype, "W": W, "skew": skew,
+            "triples": [(float(np.float32(0.1 * (1 + t % 3))), float(np.float32(0.9 if t % 2 else 0.0)),
+                         float(np.float32(1e-4 * (t % 4)))) for t in range(len(numel))],
+            "inv": float(np.float32(inv))}
+
+
+# degenerate shapes: padding far larger than the tensors (whole rows and chunks of padding),
+# the largest replica count, one element in all, only empty tensors around one small one
+DEGENERATE = {
+    "padding_rows": _fixed_case([5, 300, 1, 70], 1000, "f32", 2, True),
+    "padding_chunks_f16": _fixed_case([3, 9000, 2], 20000, "f16", 4, False, 1.0 / 1024),
+    "max_replicas": _fixed_case([513, 64, 4097], 4, "f32", 32, True),
+    "max_replicas_bf16": _fixed_case([1025, 7, 20000], 8, "bf16", 32, False, 1.0 / 128),
+    "one_element": _fixed_case([1], 1, "f32", 8, False),
+    "empties_around_one": _fixed_case([0, 0, 2, 0, 0], 64, "f16", 3, True),
+    "only_empties": _fixed_case([0, 0, 0], 4, "f32", 2, False),
+    "single_tensor_tight": _fixed_case([300001], 1, "f32", 5, True),
+}
+
+
+@pytest.mark.parametrize("name", sorted(DEGENERATE))
+def test_degenerate_list_every_form(name):
+    _run_case(DEGENERATE[name], name)
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_random_list_every_form(seed):
-    c = _draw_case(seed)
+    _run_case(_draw_case(seed), f"seed={seed}")
+
+
+def _run_case(c, label):
     rng, numel, align, dtype, W = c["rng"], c["numel"], c["align"], c["dtype"], c["W"]
-    print(f"case seed={seed} T={len(numel)} align={align} dtype={dtype} W={W} skew={c['skew']} "
+    print(f"case {label} T={len(numel)} align={align} dtype={dtype} W={W} skew={c['skew']} "
           f"elems={sum(numel)}", flush=True)
     offs = xs.bucket_layout(numel, align)
     offs_np = np.asarray(offs, dtype=np.uint64)
