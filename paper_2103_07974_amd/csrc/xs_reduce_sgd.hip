@@ -77,16 +77,24 @@ struct RowHp {
     bool uniform;
     f32x4 rec;
 };
+// The three look-ups go through the constant address space with wave-uniform indices, i.e.
+// through the scalar cache: they neither queue behind the streaming vector loads nor hold up
+// their issue.  (The tables are written once, at plan creation and by the caller before the
+// launch, and never by a kernel.)
+typedef const __attribute__((address_space(4))) uint32_t cu32;
+typedef const __attribute__((address_space(4))) uint64_t cu64;
+typedef const __attribute__((address_space(4))) f32x4 cf32x4;
+
 template <int VEC>
 __device__ __forceinline__ RowHp row_hp(const TensorHp &h, uint64_t first_vec, uint64_t n)
 {
     constexpr uint64_t ROW = (uint64_t)kThreads * VEC;
     const uint32_t row = (uint32_t)__builtin_amdgcn_readfirstlane((int)(first_vec / kThreads));
     RowHp r;
-    r.t_first = h.row_first[row];
+    r.t_first = (uint32_t)__builtin_amdgcn_readfirstlane((int)((cu32 *)h.row_first)[row]);
     const uint64_t row_end = ((uint64_t)row + 1) * ROW < n ? ((uint64_t)row + 1) * ROW : n;
-    r.uniform = h.offsets[r.t_first + 1] >= row_end;
-    r.rec = h.rec[r.t_first];
+    r.uniform = ((cu64 *)h.offsets)[r.t_first + 1] >= row_end;
+    r.rec = ((cf32x4 *)h.rec)[r.t_first];
     return r;
 }
 
