@@ -31,6 +31,8 @@
  *    xs_crossover_step) only enqueue work and return; they allocate no memory
  *    and do not synchronise.  Execution errors surface at the caller's next
  *    synchronisation.
+ *  - Calls act on the calling thread's current HIP device; every device pointer, stream and
+ *    handle passed to one call must belong to that device.
  *  - Same inputs give bit-identical outputs on every call.
  */
 #ifndef XS_H

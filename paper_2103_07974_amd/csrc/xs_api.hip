@@ -32,13 +32,15 @@ void clear_error() { t_error[0] = '\0'; }
 
 int compute_units()
 {
-    static int cached = 0;
-    if (cached > 0) return cached;
+    // one cached value per device ordinal; a benign race writes the same number twice
+    constexpr int kMaxDevices = 64;
+    static int cached[kMaxDevices] = {};
     int dev = 0, cus = 0;
     XS_HIP_TRY(hipGetDevice(&dev));
+    if (dev >= 0 && dev < kMaxDevices && cached[dev] > 0) return cached[dev];
     XS_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     if (cus <= 0) return fail(XS_ERR_HIP, "device reports %d compute units", cus);
-    cached = cus;
+    if (dev >= 0 && dev < kMaxDevices) cached[dev] = cus;
     return cus;
 }
 

@@ -21,7 +21,7 @@ void clear_error();
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// ---- device facts (queried once per process for the current device) -----------
+// ---- device facts (of the current device; queried once per device) ---------------
 int compute_units();   // > 0, or a negative xs_status
 
 // ---- tuning ---------------------------------------------------------------------
