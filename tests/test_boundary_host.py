@@ -181,3 +181,43 @@ def test_header_record_is_sixteen_bytes_of_floats():
     text = open(HEADER).read()
     start = text.index("typedef struct {\n    float lr;\n    float momentum;\n    float weight_decay;\n    float reserved;")
     assert "} xs_tensor_hparams;" in text[start:start + 300]
+
+
+def test_header_is_valid_c99_and_usable_from_c(tmp_path):
+    """The boundary is a C interface: the header must compile as strict C99 and a C program
+    must be able to call the library through it (host-only entry points here)."""
+    import subprocess
+    src = tmp_path / "use_xs.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "xs.h"
+int main(void)
+{
+    uint64_t numel[3] = {5, 0, 130}, offs[4];
+    xs_sgd_hparams hp = {0.1f, 0.9f, 1e-4f, 1.0f};
+    xs_tensor_hparams rec = {0.1f, 0.9f, 0.0f, 0.0f};
+    xs_mp_options mp = {0, XS_F16, XS_F32};
+    xs_app_desc desc;
+    memset(&desc, 0, sizeof desc);
+    (void)hp; (void)rec; (void)mp;
+    if (sizeof(rec) != 16) return 2;
+    if (xs_bucket_layout(numel, 3, 64, offs) != XS_OK) return 3;
+    if (offs[1] != 64 || offs[2] != 64 || offs[3] != 256) return 4;
+    if (xs_bucket_layout(numel, 3, 0, offs) != XS_ERR_INVALID_ARG) return 5;
+    if (strstr(xs_last_error(), "align_elems") == NULL) return 6;
+    if (xs_fuse_pack(NULL, NULL, NULL, NULL, NULL) != XS_ERR_INVALID_ARG) return 7;
+    if (xs_crossover_iteration(NULL, 0, NULL, NULL) != XS_OK) return 8;
+    printf("%s\n", xs_status_string(XS_ERR_STATE));
+    return 0;
+}
+''')
+    exe = tmp_path / "use_xs"
+    libdir = os.path.dirname(xs.LIB_PATH)
+    cmd = ["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.dirname(HEADER),
+           str(src), "-o", str(exe), "-L", libdir, "-lxs", f"-Wl,-rpath,{libdir}",
+           "-Wl,-rpath,/opt/rocm/lib", "-L", "/opt/rocm/lib"]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    res = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert res.returncode == 0, (res.returncode, res.stdout, res.stderr)
+    assert res.stdout.strip() == "XS_ERR_STATE"
