@@ -82,5 +82,6 @@ def test_training_through_the_library_reduces_the_loss():
         xs.crossover_iteration([app], cs, ss)
     torch.cuda.synchronize()
     after = loss()
+    print(f"loss {before:.4f} -> {after:.4f}", flush=True)
     assert after < 0.7 * before, (before, after)
     app.destroy()
