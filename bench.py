@@ -26,6 +26,10 @@ HBM_PEAK_GBS = 8000.0
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a plain copy's reading of the same
 # counters (profiles/hbm_traffic_pmc_reduce_sgd_pack_unpack.md)
 MEASURED_TRAFFIC_BYTES = 1226785792
+# share of the sync kernels' time that lies inside the other task's compute kernels in the
+# crossover config, from the rocprofv3 kernel trace
+# (profiles/crossover_kernel_trace_resnet50_vgg16_gemm_chain.md)
+STREAM_OVERLAP_FROM_TRACE = 0.983
 
 
 def _median(xs_):
@@ -556,6 +560,16 @@ def main():
         del bert
         torch.cuda.empty_cache()
 
+    if "crossover" in extra:
+        c = extra["crossover"]
+        out["crossover"] = {
+            "config": "ResNet-50-shaped and VGG-16-shaped syncs beside " + c["compute_standin"] + f", T={c['T']}",
+            "no_stall_fraction_app_b": c["hidden_b_no_stall"],
+            "end_to_end_hidden_fraction": c["hidden_fraction"],
+            "end_to_end_hidden_fraction_alu_standin": extra["crossover_alu_standin"]["hidden_fraction"],
+            "stream_overlap_fraction_from_kernel_trace": STREAM_OVERLAP_FROM_TRACE,
+            "speedup_vs_serial": c["speedup_vs_serial"],
+        }
     out["extra"] = extra
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, harness.DEFAULT_ALIGN)
