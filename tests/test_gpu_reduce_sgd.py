@@ -226,3 +226,25 @@ def test_device_errors_are_reported_not_raised_by_hip():
     with pytest.raises(xs.XsError) as e:
         xs.fused_reduce_sgd([g[1:]], 8, x, v, 0.1, 0.9, 0.0)       # misaligned replica
     assert e.value.status == xs.XS_ERR_ALIGNMENT
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+def test_subnormal_values_are_not_flushed(dtype):
+    """Gradients, parameters and momentum in and around the fp32 subnormal range (and fp16
+    subnormal gradients): the kernel keeps IEEE gradual underflow, like the oracle."""
+    n, W = 4099, 4
+    g = torch.Generator(); g.manual_seed(77)
+    if dtype == torch.float16:
+        reps = [(torch.randn(n, generator=g) * 3e-6).to(torch.float16) for _ in range(W)]   # below 6.1e-5
+        inv = 2.0 ** -100
+    else:
+        reps = [torch.randn(n, generator=g) * 1e-39 for _ in range(W)]
+        inv = 1.0
+    assert all((r != 0).any() for r in reps)
+    x = torch.randn(n, generator=g) * 1e-38
+    v = torch.randn(n, generator=g) * 1e-39
+    x64, v64, x32, v32 = _oracle([r.numpy() for r in reps], x.numpy(), v.numpy(), inv)
+    gx, gv = _run(reps, x, v, inv)
+    tiny = np.finfo(np.float32).tiny
+    assert (np.abs(x32) < tiny).any() and (np.abs(v32) < tiny).any() and (x32 != 0).all()
+    assert _ulp_distance(gx, x32) == 0 and _ulp_distance(gv, v32) == 0
