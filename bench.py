@@ -198,7 +198,7 @@ def time_overflow_skip(task, stream, reps=8):
 
 
 def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False, standin="gemm",
-                   cross_only=False, computes=None, label=None, streams=None):
+                   cross_only=False, computes=None, label=None, streams=None, tuning=None, rounds=5):
     """Two tasks alternate as in Algorithm 1: one computes (a stand-in for forward + backward)
     while the other synchronises on the second stream.
 
@@ -207,6 +207,7 @@ def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False,
     the kind of kernel a synchronisation wave can share a compute unit with.
     computes=(fn_a, fn_b): each task's own computation instead of a stand-in."""
     import torch
+    import bench_standin as bs
     from paper_2103_07974_amd import xs
     g = torch.Generator(device="cuda"); g.manual_seed(task_a.workload.seed + 100)
     if computes is not None:
@@ -228,17 +229,21 @@ def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False,
         sink = torch.zeros(256, device="cuda")
         target_ms, probe_iters = 12.6, 100000
         a0 = torch.cuda.Event(enable_timing=True); a1 = torch.cuda.Event(enable_timing=True)
-        xs.standin_alu(256, probe_iters, sink); torch.cuda.synchronize()
-        a0.record(); xs.standin_alu(256, probe_iters, sink); a1.record(); a1.synchronize()
+        bs.alu(256, probe_iters, sink); torch.cuda.synchronize()
+        a0.record(); bs.alu(256, probe_iters, sink); a1.record(); a1.synchronize()
         iters = max(1000, int(probe_iters * target_ms / a0.elapsed_time(a1)))
 
         def compute(stream_ptr):
-            xs.standin_alu(256, iters, sink, stream_ptr)
+            bs.alu(256, iters, sink, stream_ptr)
         label = f"one arithmetic-only kernel, 256x256 lanes, {iters} x 8 multiply-adds per lane"
     if computes is None:
         computes = (compute, compute)
-    apps = [task_a.make_app(computes[0], fused_gather=fused_gather),
-            task_b.make_app(computes[1], fused_gather=fused_gather)]
+    # `tuning`: launch settings of the synchronisations inside the two-stream schedule; the
+    # serial schedule and the stand-alone timings always use the defaults (the fastest sync)
+    apps = [task_a.make_app(computes[0], fused_gather=fused_gather, tuning=tuning),
+            task_b.make_app(computes[1], fused_gather=fused_gather, tuning=tuning)]
+    apps_alone = apps if tuning is None else [task_a.make_app(computes[0], fused_gather=fused_gather),
+                                              task_b.make_app(computes[1], fused_gather=fused_gather)]
     cs, ss = streams if streams is not None else (torch.cuda.Stream(), torch.cuda.Stream())
 
     def run_cross(record=None):
@@ -265,7 +270,7 @@ def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False,
         for t in range(T):
             for i in (0, 1):
                 computes[i](cs.cuda_stream)
-                apps[i].sync(cs)
+                apps_alone[i].sync(cs)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3
 
@@ -292,12 +297,19 @@ def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False,
             a.destroy()
         return {"T": T, "compute_standin": label, "t_cross_ms": ms,
                 "sync_kernels": "gather form" if fused_gather else "packs, reduce+SGD, unpack"}
-    run_comp(); run_serial(); run_cross()                    # warm-up of every mode
-    t_comp = _median([run_comp() for _ in range(3)])
-    t_serial = _median([run_serial() for _ in range(3)])
+    # The chip's clocks drift with its thermal and power state (the GEMM chain runs at the
+    # board's power limit), by more than the difference that is being measured; the three
+    # modes are therefore run round-robin and every figure is a median over the rounds.
+    run_comp(); run_serial(); run_cross(); run_comp(); run_serial(); run_cross()     # warm-up
     rec = []
-    t_cross = _median([run_cross(), run_cross(), run_cross(rec)])
-    sync_a, sync_b = run_sync(apps[0]), run_sync(apps[1])
+    rows = []
+    for r in range(rounds):
+        rows.append((run_comp(), run_serial(), run_cross(rec if r == rounds - 1 else None)))
+    t_comp = _median([x[0] for x in rows])
+    t_serial = _median([x[1] for x in rows])
+    t_cross = _median([x[2] for x in rows])
+    per_round_hidden = [1.0 - (x[2] - x[0]) / (x[1] - x[0]) for x in rows if x[1] > x[0]]
+    sync_a, sync_b = run_sync(apps_alone[0]), run_sync(apps_alone[1])
     sum_sync = t_serial - t_comp
     # event view: how long each synchronisation ran past the end of the computation beside it
     exposed = {0: 0.0, 1: 0.0}; count = {0: 0, 1: 0}; late = {0: 0, 1: 0}
@@ -314,13 +326,15 @@ def crossover_pair(task_a, task_b, T=20, chain=16, dim=8192, fused_gather=False,
         "compute_chain_ms": t_comp / (2 * T),
         "comm_comp_ratio_a": sync_a / (t_comp / (2 * T)), "comm_comp_ratio_b": sync_b / (t_comp / (2 * T)),
         "hidden_fraction": 1.0 - (t_cross - t_comp) / sum_sync if sum_sync > 0 else None,
+        "hidden_fraction_median_of_rounds": _median(per_round_hidden) if per_round_hidden else None,
+        "hidden_fraction_per_round": per_round_hidden, "rounds": rounds,
         "speedup_vs_serial": t_serial / t_cross,
         "syncs_finished_before_compute_end": {"a": count[0] - late[0], "b": count[1] - late[1],
                                               "of_a": count[0], "of_b": count[1]},
         "hidden_b_no_stall": 1.0 - exposed[1] / (count[1] * sync_b) if count[1] else None,
         "hidden_a_no_stall": 1.0 - exposed[0] / (count[0] * sync_a) if count[0] else None,
     }
-    for a in apps:
+    for a in set(apps + apps_alone):
         a.destroy()
     return res
 

@@ -160,6 +160,10 @@ int xs_fused_reduce_sgd(const void *const *replica_buckets, uint32_t W, int grad
  *   model_copy        xs_fused_reduce_sgd_mp only: device, 16-byte aligned, n_elems half-
  *                     precision elements in bucket layout, or NULL.  Receives the updated
  *                     parameters rounded to nearest even, in the same pass (+2 bytes/element).
+ *                     XS_ERR_UNSUPPORTED together with in-kernel overflow detection
+ *                     (out-of-place outputs and found_inf both given): the copy is the live
+ *                     model, and a pass that is still deciding whether the step is skipped
+ *                     must not overwrite part of it.
  *   model_copy_dtype  XS_F16 or XS_BF16.
  *   view_dtype        xs_fused_gather_reduce_sgd_mp only: element type of the per-layer views
  *                     that param_tensor_ptrs point to: XS_F32, XS_F16 or XS_BF16.
@@ -246,6 +250,59 @@ int xs_fused_gather_reduce_sgd_pt(const xs_plan *gradient_plan, const void *cons
                                   int32_t *found_inf, const xs_mp_options *mp, void *hip_stream);
 
 /* ------------------------------------------------------------------------
+ * Launch settings.  xs_tuning_set changes the process-wide values that every call outside an
+ * xs_app reads (one consistent snapshot per call; setting a value while another thread
+ * launches is safe, that launch sees the old or the new value).  A task that must be
+ * launched differently from the rest of the process - e.g. paced so that it runs beside
+ * another task's computation - carries its own values in xs_app_desc.tuning instead.
+ * The defaults are the measured best for a synchronisation that has MI355X to itself.
+ * Returns XS_ERR_INVALID_ARG for an unknown key or an out-of-range value.
+ */
+typedef enum {
+    XS_TUNE_REDUCE_WG_PER_CU = 0,   /* reduce kernels: workgroups per compute unit for a grid-stride
+                                       launch; 0 (default) = one 16-byte vector per lane, no loop */
+    XS_TUNE_COPY_WG_PER_CU = 1,     /* pack/unpack: workgroups per compute unit of a persistent grid;
+                                       0 (default) = one 16 KiB chunk per workgroup, dispatched in
+                                       bucket order (a few chunks when the tensor table is large) */
+    XS_TUNE_NT_GRADS = 2,           /* bucket-form reduce: non-temporal gradient loads (0/1, default 1) */
+    XS_TUNE_NT_STATE = 3,           /* bucket-form reduce: non-temporal parameter/momentum accesses (0/1, default 1) */
+    XS_TUNE_REDUCE_LDS_RESERVE = 4, /* bytes of LDS reserved per reduce workgroup; the kernel uses no
+                                       LDS, the reservation caps how many workgroups share a compute
+                                       unit; -1 (default) = 16384: ten one-wave workgroups per compute unit */
+    XS_TUNE_REDUCE_MAX_WG = 5,      /* absolute cap on reduce workgroups, 0 = none */
+    XS_TUNE_COPY_MAX_WG = 6,        /* absolute cap on pack/unpack workgroups, 0 = none */
+    XS_TUNE_COPY_NT = 7,            /* pack/unpack: non-temporal accesses (0/1, default 1) */
+    XS_TUNE_GATHER_LDS_RESERVE = 8, /* as 4 for the gathering form; -1 = 8192 fp32, 16384 half */
+    XS_TUNE_COPY_LDS_RESERVE = 9,   /* pack/unpack: bytes of LDS reserved per 256-lane workgroup beyond its
+                                       tensor table; -1 (default) = 32768 */
+    XS_TUNE_REDUCE_WAVES_PER_WG = 10, /* reduce kernels: wavefronts per workgroup, 1 (default), 2 or 4.
+                                       The four wavefronts of a 4-wave workgroup land on the four SIMDs
+                                       of one compute unit */
+    XS_TUNE_REDUCE_SMALL = 11,      /* bucket-form reduce: 0 (default) = the kernel specialised for W with all
+                                       W + 2 loads in flight (54 to 85 registers per lane); 1 = the
+                                       generic-W kernel whatever W is: four replica loads in flight at a
+                                       time, 28 (fp32) to 47 (fp16) registers per lane, same arithmetic */
+    XS_TUNE_COUNT = 12
+} xs_tuning_key;
+int xs_tuning_set(int key, int value);
+int xs_tuning_get(int key, int *value_out);
+
+/* Fills values_out[XS_TUNE_COUNT] with a named set of launch settings for xs_app_desc.tuning.
+ *   XS_PRESET_ALONE           the defaults: the synchronisation has the GPU to itself
+ *   XS_PRESET_BESIDE_COMPUTE  the synchronisation shares every compute unit with another
+ *                             task's kernels (Section 2.1): one 4-wave workgroup per compute
+ *                             unit at a time (one wavefront per SIMD, at most 48 registers
+ *                             per lane in the bucket form) holding an LDS reservation of
+ *                             82 KiB, so that a second synchronisation workgroup never fits
+ *                             while 78 KiB of LDS, 7/8 of the wave slots and 29/32 of the
+ *                             register file stay free for the other task's workgroups at
+ *                             all times
+ * XS_ERR_INVALID_ARG for an unknown preset or a NULL pointer.
+ */
+typedef enum { XS_PRESET_ALONE = 0, XS_PRESET_BESIDE_COMPUTE = 1 } xs_tuning_preset_id;
+int xs_tuning_preset(int preset, int32_t *values_out /* XS_TUNE_COUNT */);
+
+/* ------------------------------------------------------------------------
  * Training task ("distributed task i" of Algorithm 1) as seen by the scheduler.
  * All pointers in the descriptor are copied or referenced as stated and must
  * stay valid until xs_app_destroy.
@@ -265,7 +322,7 @@ typedef struct {
     float *momentum;                         /* device, bucket layout, fp32           */
     void *const *param_tensor_ptrs;          /* device pointer table of parameter views */
     xs_sgd_hparams hp;
-    int32_t *found_inf;                      /* device, may be NULL                   */
+    int32_t *found_inf;                      /* device, may be NULL; see below        */
     xs_compute_fn compute;                   /* may be NULL (no compute enqueued)     */
     void *compute_ctx;
     uint32_t flags;                          /* XS_APP_* bits                         */
@@ -273,12 +330,28 @@ typedef struct {
                                                 with XS_APP_FUSED_GATHER, else may be NULL */
     const xs_tensor_hparams *tensor_hp;      /* device, one record per tensor, or NULL:
                                                 hp's lr/momentum/weight_decay for all     */
+    const int32_t *tuning;                   /* host, XS_TUNE_COUNT launch settings copied at
+                                                xs_app_create (see xs_tuning_preset), or NULL:
+                                                the process-wide settings at every call   */
 } xs_app_desc;
 
 /* Synchronise with xs_fused_gather_reduce_sgd (gradients read from the per-layer tensors,
  * parameters written to the views in the same pass) instead of W packs + reduce + unpack.
- * replica_buckets and grad_tensor_ptrs are then unused and may be NULL. */
+ * replica_buckets and grad_tensor_ptrs are then unused and may be NULL.  No pack runs in this
+ * form, so nothing could raise found_inf before the in-place pass: xs_app_create returns
+ * XS_ERR_UNSUPPORTED when found_inf is given together with this flag. */
 #define XS_APP_FUSED_GATHER 1u
+
+/* xs_app_desc.found_inf - loss-scale overflow inside the scheduler (beyond the paper).
+ * The W packs of a synchronisation raise the flag when any gradient element of any worker is
+ * +-inf or NaN; the reduce + SGD enqueued behind them then leaves parameters and momentum
+ * untouched, and the unpack hands the unchanged parameters back.  The library never clears
+ * the flag: while it is up every later synchronisation of the task is skipped as well.
+ * The caller clears it on the SYNC stream (a one-word fill kernel or copy enqueued there is
+ * ordered after the synchronisation that read it and before the next one), typically right
+ * after it has looked at the flag's value behind sync_done (xs_app_wait_sync) to rescale
+ * the loss.  A caller that never looks keeps the enqueue-only contract of Algorithm 1 and
+ * simply loses every step after the first overflow. */
 
 typedef struct xs_app xs_app;
 int xs_app_create(const xs_app_desc *desc, xs_app **out);   /* creates two HIP events */
@@ -322,41 +395,6 @@ int xs_crossover_finish(xs_app *const *apps, uint32_t n_apps, void *sync_stream)
 
 /* Makes hip_stream wait for app's last enqueued synchronisation (no-op if none). */
 int xs_app_wait_sync(xs_app *app, void *hip_stream);
-
-/* ------------------------------------------------------------------------
- * Arithmetic-only compute stand-in for overlap measurements (Section 2.1: one task
- * computes while the other synchronises): `workgroups` workgroups of 256 lanes each run
- * 8*iters dependent multiply-adds per lane and touch no memory.  sink: device, at least
- * 256 floats, practically never written.  Enqueue only.
- */
-int xs_standin_alu(uint32_t workgroups, uint32_t iters, float *sink, void *hip_stream);
-
-/* ------------------------------------------------------------------------
- * Launch tuning (process-wide; the defaults are the measured best for MI355X).
- * Returns XS_ERR_INVALID_ARG for an unknown key or an out-of-range value.
- */
-typedef enum {
-    XS_TUNE_REDUCE_WG_PER_CU = 0,   /* reduce kernels: workgroups per compute unit for a grid-stride
-                                       launch; 0 (default) = one 16-byte vector per lane, no loop */
-    XS_TUNE_COPY_WG_PER_CU = 1,     /* pack/unpack: workgroups per compute unit of a persistent grid;
-                                       0 (default) = one 16 KiB chunk per workgroup, dispatched in
-                                       bucket order (a few chunks when the tensor table is large) */
-    XS_TUNE_NT_GRADS = 2,           /* bucket-form reduce: non-temporal gradient loads (0/1, default 1) */
-    XS_TUNE_NT_STATE = 3,           /* bucket-form reduce: non-temporal parameter/momentum accesses (0/1, default 1) */
-    XS_TUNE_REDUCE_LDS_RESERVE = 4, /* bytes of LDS reserved per reduce workgroup; the kernel uses no
-                                       LDS, the reservation caps how many wavefronts share a compute
-                                       unit; -1 (default) = 16384: ten one-wave workgroups per compute unit */
-    XS_TUNE_REDUCE_MAX_WG = 5,      /* absolute cap on reduce workgroups, 0 = none: paces a */
-    XS_TUNE_COPY_MAX_WG = 6,        /*   synchronisation that runs beside another task's computation */
-    XS_TUNE_COPY_NT = 7,            /* pack/unpack: non-temporal accesses (0/1, default 1) */
-    XS_TUNE_GATHER_LDS_RESERVE = 8, /* as 4 for the gathering form; -1 = 8192 fp32, 16384 half */
-    XS_TUNE_COPY_LDS_RESERVE = 9,   /* pack/unpack: bytes of LDS reserved per 256-lane workgroup beyond its
-                                       tensor table (caps the workgroups per compute unit so that another
-                                       task's kernels can still be placed beside them); -1 (default) = 32768 */
-    XS_TUNE_COUNT = 10
-} xs_tuning_key;
-int xs_tuning_set(int key, int value);
-int xs_tuning_get(int key, int *value_out);
 
 #ifdef __cplusplus
 }

@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
 #include <new>
 #include <vector>
 
@@ -44,10 +45,58 @@ int compute_units()
     return cus;
 }
 
-// -1 = chosen per gradient dtype at launch (see launch_reduce_sgd)
-Tuning g_tuning = {/*reduce_wg_per_cu*/ 0, /*copy_wg_per_cu*/ 0, /*nt_grads*/ 1, /*nt_state*/ 1,
-                   /*reduce_lds_reserve*/ -1, /*reduce_max_wg*/ 0, /*copy_max_wg*/ 0,
-                   /*copy_nt*/ 1, /*gather_lds_reserve*/ -1, /*copy_lds_reserve*/ -1};
+// process-wide launch settings; -1 = chosen per gradient dtype at launch
+static const int kTuningDefault[XS_TUNE_COUNT] = {/*reduce_wg_per_cu*/ 0, /*copy_wg_per_cu*/ 0,
+                                                 /*nt_grads*/ 1, /*nt_state*/ 1,
+                                                 /*reduce_lds_reserve*/ -1, /*reduce_max_wg*/ 0,
+                                                 /*copy_max_wg*/ 0, /*copy_nt*/ 1,
+                                                 /*gather_lds_reserve*/ -1, /*copy_lds_reserve*/ -1,
+                                                 /*reduce_waves_per_wg*/ 1, /*reduce_small*/ 0};
+struct TuningRange {
+    int lo, hi;
+};
+static const TuningRange kTuningRange[XS_TUNE_COUNT] = {
+    {0, 64},          // XS_TUNE_REDUCE_WG_PER_CU
+    {0, 4096},        // XS_TUNE_COPY_WG_PER_CU
+    {0, 1},           // XS_TUNE_NT_GRADS
+    {0, 1},           // XS_TUNE_NT_STATE
+    {-1, 131072},     // XS_TUNE_REDUCE_LDS_RESERVE
+    {0, 0x7fffffff},  // XS_TUNE_REDUCE_MAX_WG
+    {0, 0x7fffffff},  // XS_TUNE_COPY_MAX_WG
+    {0, 1},           // XS_TUNE_COPY_NT
+    {-1, 131072},     // XS_TUNE_GATHER_LDS_RESERVE
+    {-1, 131072},     // XS_TUNE_COPY_LDS_RESERVE
+    {1, 4},           // XS_TUNE_REDUCE_WAVES_PER_WG (1, 2 or 4)
+    {0, 1},           // XS_TUNE_REDUCE_SMALL
+};
+static std::atomic<int> g_tuning[XS_TUNE_COUNT] = {
+    {kTuningDefault[0]}, {kTuningDefault[1]}, {kTuningDefault[2]}, {kTuningDefault[3]},
+    {kTuningDefault[4]}, {kTuningDefault[5]}, {kTuningDefault[6]}, {kTuningDefault[7]},
+    {kTuningDefault[8]}, {kTuningDefault[9]}, {kTuningDefault[10]}, {kTuningDefault[11]}};
+
+static bool tuning_value_ok(int key, int value)
+{
+    if (value < kTuningRange[key].lo || value > kTuningRange[key].hi) return false;
+    return key != XS_TUNE_REDUCE_WAVES_PER_WG || value != 3;
+}
+
+Tuning tuning_now()
+{
+    Tuning t;
+    for (int k = 0; k < XS_TUNE_COUNT; ++k) t.v[k] = g_tuning[k].load(std::memory_order_relaxed);
+    return t;
+}
+
+int tuning_check(const int32_t *values, Tuning *out)
+{
+    for (int k = 0; k < XS_TUNE_COUNT; ++k) {
+        if (!tuning_value_ok(k, values[k]))
+            return fail(XS_ERR_INVALID_ARG, "launch setting %d = %d is outside [%d, %d]", k, values[k],
+                        kTuningRange[k].lo, kTuningRange[k].hi);
+        out->v[k] = values[k];
+    }
+    return XS_OK;
+}
 
 }  // namespace xs
 
@@ -70,33 +119,14 @@ extern "C" const char *xs_status_string(int status)
 
 extern "C" const char *xs_last_error(void) { return t_error; }
 
-namespace {
-struct TuningSlot {
-    int xs::Tuning::*field;
-    int lo, hi;
-};
-const TuningSlot kTuning[XS_TUNE_COUNT] = {
-    {&xs::Tuning::reduce_wg_per_cu, 0, 64},       // XS_TUNE_REDUCE_WG_PER_CU
-    {&xs::Tuning::copy_wg_per_cu, 0, 4096},       // XS_TUNE_COPY_WG_PER_CU
-    {&xs::Tuning::nt_grads, 0, 1},                // XS_TUNE_NT_GRADS
-    {&xs::Tuning::nt_state, 0, 1},                // XS_TUNE_NT_STATE
-    {&xs::Tuning::reduce_lds_reserve, -1, 65536}, // XS_TUNE_REDUCE_LDS_RESERVE
-    {&xs::Tuning::reduce_max_wg, 0, 0x7fffffff},  // XS_TUNE_REDUCE_MAX_WG
-    {&xs::Tuning::copy_max_wg, 0, 0x7fffffff},    // XS_TUNE_COPY_MAX_WG
-    {&xs::Tuning::copy_nt, 0, 1},                 // XS_TUNE_COPY_NT
-    {&xs::Tuning::gather_lds_reserve, -1, 65536}, // XS_TUNE_GATHER_LDS_RESERVE
-    {&xs::Tuning::copy_lds_reserve, -1, 65536},   // XS_TUNE_COPY_LDS_RESERVE
-};
-}  // namespace
-
 extern "C" int xs_tuning_set(int key, int value)
 {
     if (key < 0 || key >= XS_TUNE_COUNT)
         return fail(XS_ERR_INVALID_ARG, "xs_tuning_set: unknown key %d", key);
-    if (value < kTuning[key].lo || value > kTuning[key].hi)
+    if (!tuning_value_ok(key, value))
         return fail(XS_ERR_INVALID_ARG, "xs_tuning_set: value %d out of range [%d, %d] for key %d",
-                    value, kTuning[key].lo, kTuning[key].hi, key);
-    g_tuning.*(kTuning[key].field) = value;
+                    value, kTuningRange[key].lo, kTuningRange[key].hi, key);
+    g_tuning[key].store(value, std::memory_order_relaxed);
     return XS_OK;
 }
 
@@ -105,8 +135,29 @@ extern "C" int xs_tuning_get(int key, int *value_out)
     if (!value_out) return fail(XS_ERR_INVALID_ARG, "xs_tuning_get: value_out is NULL");
     if (key < 0 || key >= XS_TUNE_COUNT)
         return fail(XS_ERR_INVALID_ARG, "xs_tuning_get: unknown key %d", key);
-    *value_out = g_tuning.*(kTuning[key].field);
+    *value_out = g_tuning[key].load(std::memory_order_relaxed);
     return XS_OK;
+}
+
+// Launch settings for a synchronisation that shares the compute units with another task's
+// kernels (Section 2.1).  MI355X: 160 KiB of LDS per compute unit; a reservation of 82 KiB
+// admits exactly one synchronisation workgroup per compute unit and leaves 78 KiB to the other task.
+extern "C" int xs_tuning_preset(int preset, int32_t *values_out)
+{
+    if (!values_out) return fail(XS_ERR_INVALID_ARG, "xs_tuning_preset: values_out is NULL");
+    for (int k = 0; k < XS_TUNE_COUNT; ++k) values_out[k] = kTuningDefault[k];
+    switch (preset) {
+    case XS_PRESET_ALONE: return XS_OK;
+    case XS_PRESET_BESIDE_COMPUTE:
+        values_out[XS_TUNE_REDUCE_WAVES_PER_WG] = 4;
+        values_out[XS_TUNE_REDUCE_LDS_RESERVE] = 82 * 1024;
+        values_out[XS_TUNE_GATHER_LDS_RESERVE] = 82 * 1024;
+        values_out[XS_TUNE_COPY_LDS_RESERVE] = 82 * 1024;
+        values_out[XS_TUNE_REDUCE_SMALL] = 1;   // 28-47 registers per lane
+        values_out[XS_TUNE_COPY_NT] = 0;        // unpack: 46 registers instead of 50
+        return XS_OK;
+    default: return fail(XS_ERR_INVALID_ARG, "xs_tuning_preset: unknown preset %d", preset);
+    }
 }
 
 // Section 2.1, tensor fusion: tensors laid end to end, each start rounded up.
@@ -257,13 +308,13 @@ extern "C" int xs_fuse_pack(const xs_plan *plan, const void *const *tensor_ptrs,
     if (found_inf && ((uintptr_t)found_inf & 3u))
         return fail(XS_ERR_ALIGNMENT, "xs_fuse_pack: found_inf is not 4-byte aligned");
     const void *table = tensor_ptrs;
-    return launch_pack(plan, &table, &bucket, 1, found_inf, (hipStream_t)hip_stream);
+    return launch_pack(tuning_now(), plan, &table, &bucket, 1, found_inf, (hipStream_t)hip_stream);
 }
 
 // The W workers' packs of one synchronisation in a single launch.
-extern "C" int xs_fuse_pack_many(const xs_plan *plan, const void *const *const *tensor_ptr_tables,
-                                 void *const *buckets, uint32_t n, int32_t *found_inf,
-                                 void *hip_stream)
+int xs::fuse_pack_many_impl(const Tuning &tn, const xs_plan *plan,
+                            const void *const *const *tensor_ptr_tables, void *const *buckets,
+                            uint32_t n, int32_t *found_inf, hipStream_t stream)
 {
     if (!plan || plan->magic != XS_PLAN_MAGIC)
         return fail(XS_ERR_INVALID_ARG, "xs_fuse_pack_many: plan is NULL or not a plan");
@@ -280,12 +331,19 @@ extern "C" int xs_fuse_pack_many(const xs_plan *plan, const void *const *const *
         if (!aligned16(buckets[i]))
             return fail(XS_ERR_ALIGNMENT, "xs_fuse_pack_many: buckets[%u] is not 16-byte aligned", i);
     }
-    return launch_pack(plan, (const void *const *)tensor_ptr_tables, buckets, n, found_inf,
-                       (hipStream_t)hip_stream);
+    return launch_pack(tn, plan, (const void *const *)tensor_ptr_tables, buckets, n, found_inf, stream);
 }
 
-extern "C" int xs_fuse_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,
-                              void *hip_stream)
+extern "C" int xs_fuse_pack_many(const xs_plan *plan, const void *const *const *tensor_ptr_tables,
+                                 void *const *buckets, uint32_t n, int32_t *found_inf,
+                                 void *hip_stream)
+{
+    return fuse_pack_many_impl(tuning_now(), plan, tensor_ptr_tables, buckets, n, found_inf,
+                               (hipStream_t)hip_stream);
+}
+
+int xs::fuse_unpack_impl(const Tuning &tn, const xs_plan *plan, const void *bucket,
+                         void *const *tensor_ptrs, hipStream_t stream)
 {
     if (!plan || plan->magic != XS_PLAN_MAGIC)
         return fail(XS_ERR_INVALID_ARG, "xs_fuse_unpack: plan is NULL or not a plan");
@@ -293,7 +351,13 @@ extern "C" int xs_fuse_unpack(const xs_plan *plan, const void *bucket, void *con
     if (!bucket) return fail(XS_ERR_INVALID_ARG, "xs_fuse_unpack: bucket is NULL");
     if (!tensor_ptrs) return fail(XS_ERR_INVALID_ARG, "xs_fuse_unpack: tensor_ptrs is NULL");
     if (!aligned16(bucket)) return fail(XS_ERR_ALIGNMENT, "xs_fuse_unpack: bucket is not 16-byte aligned");
-    return launch_unpack(plan, bucket, tensor_ptrs, (hipStream_t)hip_stream);
+    return launch_unpack(tn, plan, bucket, tensor_ptrs, stream);
+}
+
+extern "C" int xs_fuse_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,
+                              void *hip_stream)
+{
+    return fuse_unpack_impl(tuning_now(), plan, bucket, tensor_ptrs, (hipStream_t)hip_stream);
 }
 
 // ---- Algorithm 1, "Receive averaged gradients" + "Model Update" ----------------------
@@ -306,12 +370,12 @@ static bool overlaps(const void *a, uint64_t a_bytes, const void *b, uint64_t b_
 static bool is_half_dtype(int dtype) { return dtype == XS_F16 || dtype == XS_BF16; }
 
 // plan + tensor_hp: per-tensor records (both NULL for the single-triple entry points)
-static int reduce_sgd_checked(const xs_plan *plan, const xs_tensor_hparams *tensor_hp,
-                              const void *const *replica_buckets, uint32_t W, int grad_dtype,
-                              uint64_t n_elems, float *params, float *momentum,
-                              float *params_out, float *momentum_out,
-                              const xs_sgd_hparams *hp, int32_t *found_inf,
-                              const xs_mp_options *mp, void *hip_stream)
+int xs::reduce_sgd_impl(const Tuning &tn, const xs_plan *plan, const xs_tensor_hparams *tensor_hp,
+                        const void *const *replica_buckets, uint32_t W, int grad_dtype,
+                        uint64_t n_elems, float *params, float *momentum,
+                        float *params_out, float *momentum_out,
+                        const xs_sgd_hparams *hp, int32_t *found_inf,
+                        const xs_mp_options *mp, hipStream_t stream)
 {
     void *model_copy = mp ? mp->model_copy : nullptr;
     const int model_copy_dtype = mp ? mp->model_copy_dtype : XS_F16;
@@ -333,6 +397,10 @@ static int reduce_sgd_checked(const xs_plan *plan, const xs_tensor_hparams *tens
     if (!replica_buckets || !params || !momentum)
         return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd: replica_buckets/params/momentum is NULL");
     const bool out_of_place = params_out != nullptr;
+    if (model_copy && out_of_place && found_inf)
+        return fail(XS_ERR_UNSUPPORTED,
+                    "xs_fused_reduce_sgd: model_copy cannot be written by a pass that is still deciding "
+                    "whether the step is skipped (out-of-place outputs with found_inf)");
     if (!aligned16(params) || !aligned16(momentum) ||
         (out_of_place && (!aligned16(params_out) || !aligned16(momentum_out))))
         return fail(XS_ERR_ALIGNMENT, "xs_fused_reduce_sgd: params/momentum pointers must be 16-byte aligned");
@@ -369,12 +437,11 @@ static int reduce_sgd_checked(const xs_plan *plan, const xs_tensor_hparams *tens
             if (overlaps(tensor_hp, hbytes, state[a], sbytes))
                 return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd_pt: tensor_hp overlaps an output buffer");
     }
-    return launch_reduce_sgd(replica_buckets, W, grad_dtype, n_elems, params, momentum,
+    return launch_reduce_sgd(tn, replica_buckets, W, grad_dtype, n_elems, params, momentum,
                              out_of_place ? params_out : params,
                              out_of_place ? momentum_out : momentum, *hp, found_inf,
                              /*detect=*/out_of_place && found_inf != nullptr, model_copy,
-                             model_copy_dtype, tensor_hp ? plan : nullptr, tensor_hp,
-                             (hipStream_t)hip_stream);
+                             model_copy_dtype, tensor_hp ? plan : nullptr, tensor_hp, stream);
 }
 
 extern "C" int xs_fused_reduce_sgd_mp(const void *const *replica_buckets, uint32_t W, int grad_dtype,
@@ -383,16 +450,17 @@ extern "C" int xs_fused_reduce_sgd_mp(const void *const *replica_buckets, uint32
                                       const xs_sgd_hparams *hp, int32_t *found_inf,
                                       const xs_mp_options *mp, void *hip_stream)
 {
-    return reduce_sgd_checked(nullptr, nullptr, replica_buckets, W, grad_dtype, n_elems, params,
-                              momentum, params_out, momentum_out, hp, found_inf, mp, hip_stream);
+    return reduce_sgd_impl(tuning_now(), nullptr, nullptr, replica_buckets, W, grad_dtype, n_elems,
+                           params, momentum, params_out, momentum_out, hp, found_inf, mp,
+                           (hipStream_t)hip_stream);
 }
 
 // One (lr, momentum, weight decay) record per tensor of the plan the buckets were packed with.
-extern "C" int xs_fused_reduce_sgd_pt(const xs_plan *gradient_plan, const void *const *replica_buckets,
-                                      uint32_t W, float *params, float *momentum,
-                                      float *params_out, float *momentum_out,
-                                      const xs_tensor_hparams *tensor_hp, float inv_loss_scale,
-                                      int32_t *found_inf, const xs_mp_options *mp, void *hip_stream)
+int xs::reduce_sgd_pt_impl(const Tuning &tn, const xs_plan *gradient_plan,
+                           const void *const *replica_buckets, uint32_t W, float *params,
+                           float *momentum, float *params_out, float *momentum_out,
+                           const xs_tensor_hparams *tensor_hp, float inv_loss_scale,
+                           int32_t *found_inf, const xs_mp_options *mp, hipStream_t stream)
 {
     if (!gradient_plan || gradient_plan->magic != XS_PLAN_MAGIC)
         return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd_pt: plan is NULL or not a plan");
@@ -401,9 +469,20 @@ extern "C" int xs_fused_reduce_sgd_pt(const xs_plan *gradient_plan, const void *
     if (!aligned16(tensor_hp))
         return fail(XS_ERR_ALIGNMENT, "xs_fused_reduce_sgd_pt: tensor_hp is not 16-byte aligned");
     const xs_sgd_hparams hp = {0.f, 0.f, 0.f, inv_loss_scale};
-    return reduce_sgd_checked(gradient_plan, tensor_hp, replica_buckets, W, gradient_plan->dtype,
-                              gradient_plan->bucket_elems, params, momentum, params_out,
-                              momentum_out, &hp, found_inf, mp, hip_stream);
+    return reduce_sgd_impl(tn, gradient_plan, tensor_hp, replica_buckets, W, gradient_plan->dtype,
+                           gradient_plan->bucket_elems, params, momentum, params_out,
+                           momentum_out, &hp, found_inf, mp, stream);
+}
+
+extern "C" int xs_fused_reduce_sgd_pt(const xs_plan *gradient_plan, const void *const *replica_buckets,
+                                      uint32_t W, float *params, float *momentum,
+                                      float *params_out, float *momentum_out,
+                                      const xs_tensor_hparams *tensor_hp, float inv_loss_scale,
+                                      int32_t *found_inf, const xs_mp_options *mp, void *hip_stream)
+{
+    return reduce_sgd_pt_impl(tuning_now(), gradient_plan, replica_buckets, W, params, momentum,
+                              params_out, momentum_out, tensor_hp, inv_loss_scale, found_inf, mp,
+                              (hipStream_t)hip_stream);
 }
 
 extern "C" int xs_fused_reduce_sgd(const void *const *replica_buckets, uint32_t W, int grad_dtype,
@@ -416,12 +495,12 @@ extern "C" int xs_fused_reduce_sgd(const void *const *replica_buckets, uint32_t 
 }
 
 // ---- the same pass reading the per-layer gradient tensors directly ----------------------
-static int gather_reduce_sgd_checked(const xs_plan *gradient_plan, const void *const *grad_ptrs,
-                                     uint32_t W, float *params, float *momentum,
-                                     float *params_out, float *momentum_out,
-                                     void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
-                                     const xs_tensor_hparams *tensor_hp, int32_t *found_inf,
-                                     const xs_mp_options *mp, void *hip_stream)
+int xs::gather_reduce_sgd_impl(const Tuning &tn, const xs_plan *gradient_plan,
+                               const void *const *grad_ptrs, uint32_t W, float *params,
+                               float *momentum, float *params_out, float *momentum_out,
+                               void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
+                               const xs_tensor_hparams *tensor_hp, int32_t *found_inf,
+                               const xs_mp_options *mp, hipStream_t stream)
 {
     const int view_dtype = mp ? mp->view_dtype : XS_F32;
     if (view_dtype != XS_F32 && !is_half_dtype(view_dtype))
@@ -469,11 +548,10 @@ static int gather_reduce_sgd_checked(const xs_plan *gradient_plan, const void *c
             if (overlaps(tensor_hp, hbytes, state[a], sbytes))
                 return fail(XS_ERR_INVALID_ARG, "xs_fused_gather_reduce_sgd_pt: tensor_hp overlaps an output buffer");
     }
-    return launch_gather_reduce_sgd(gradient_plan, grad_ptrs, W, params, momentum,
+    return launch_gather_reduce_sgd(tn, gradient_plan, grad_ptrs, W, params, momentum,
                                     out_of_place ? params_out : params,
                                     out_of_place ? momentum_out : momentum, param_tensor_ptrs,
-                                    view_dtype, *hp, tensor_hp, found_inf, detect,
-                                    (hipStream_t)hip_stream);
+                                    view_dtype, *hp, tensor_hp, found_inf, detect, stream);
 }
 
 extern "C" int xs_fused_gather_reduce_sgd_mp(const xs_plan *gradient_plan, const void *const *grad_ptrs,
@@ -483,9 +561,9 @@ extern "C" int xs_fused_gather_reduce_sgd_mp(const xs_plan *gradient_plan, const
                                              int32_t *found_inf, const xs_mp_options *mp,
                                              void *hip_stream)
 {
-    return gather_reduce_sgd_checked(gradient_plan, grad_ptrs, W, params, momentum, params_out,
-                                     momentum_out, param_tensor_ptrs, hp, nullptr, found_inf, mp,
-                                     hip_stream);
+    return gather_reduce_sgd_impl(tuning_now(), gradient_plan, grad_ptrs, W, params, momentum,
+                                  params_out, momentum_out, param_tensor_ptrs, hp, nullptr, found_inf,
+                                  mp, (hipStream_t)hip_stream);
 }
 
 extern "C" int xs_fused_gather_reduce_sgd_pt(const xs_plan *gradient_plan, const void *const *grad_ptrs,
@@ -500,9 +578,9 @@ extern "C" int xs_fused_gather_reduce_sgd_pt(const xs_plan *gradient_plan, const
         !tensor_hp)
         return fail(XS_ERR_INVALID_ARG, "xs_fused_gather_reduce_sgd_pt: tensor_hp is NULL");
     const xs_sgd_hparams hp = {0.f, 0.f, 0.f, inv_loss_scale};
-    return gather_reduce_sgd_checked(gradient_plan, grad_ptrs, W, params, momentum, params_out,
-                                     momentum_out, param_tensor_ptrs, &hp, tensor_hp, found_inf, mp,
-                                     hip_stream);
+    return gather_reduce_sgd_impl(tuning_now(), gradient_plan, grad_ptrs, W, params, momentum,
+                                  params_out, momentum_out, param_tensor_ptrs, &hp, tensor_hp,
+                                  found_inf, mp, (hipStream_t)hip_stream);
 }
 
 extern "C" int xs_fused_gather_reduce_sgd(const xs_plan *gradient_plan, const void *const *grad_ptrs,

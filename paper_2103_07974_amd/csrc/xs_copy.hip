@@ -188,7 +188,7 @@ __global__ __launch_bounds__(kCopyThreads) void copy_kernel(
 }
 
 template <bool UNPACK, bool DETECT, int DT>
-static int launch_copy(const xs_plan *plan, const void *const *tables, void *const *buckets,
+static int launch_copy(const Tuning &tn, const xs_plan *plan, const void *const *tables, void *const *buckets,
                        uint32_t n_pairs, int32_t *found_inf, hipStream_t stream)
 {
     const int cus = compute_units();
@@ -207,23 +207,23 @@ static int launch_copy(const xs_plan *plan, const void *const *tables, void *con
     // tight).  Every workgroup stages the chunk-prefix table in LDS first, so lists with a table
     // beyond 4 KiB give each workgroup one more chunk per further 4 KiB to amortise that.
     uint64_t blocks;
-    if (g_tuning.copy_wg_per_cu > 0) {
-        blocks = (uint64_t)cus * (uint64_t)g_tuning.copy_wg_per_cu;
+    if (tn.copy_wg_per_cu() > 0) {
+        blocks = (uint64_t)cus * (uint64_t)tn.copy_wg_per_cu();
     } else {
         const uint64_t per_wg = lds_bytes > 4096 ? (lds_bytes + 4095) / 4096 : 1;
         blocks = (n_items + per_wg - 1) / per_wg;
     }
-    if (g_tuning.copy_max_wg > 0 && blocks > (uint64_t)g_tuning.copy_max_wg)
-        blocks = (uint64_t)g_tuning.copy_max_wg;
+    if (tn.copy_max_wg() > 0 && blocks > (uint64_t)tn.copy_max_wg())
+        blocks = (uint64_t)tn.copy_max_wg();
     if (blocks > n_items) blocks = n_items;
     if (blocks > 0x7fffffffull) blocks = 0x7fffffffull;   // the loop covers the rest
-    const bool nt = g_tuning.copy_nt != 0;
+    const bool nt = tn.copy_nt();
     const dim3 grid((unsigned)blocks), block(kCopyThreads);
     // Measured on MI355X: five 256-lane workgroups per compute unit (32 KiB of LDS each, only the
     // table's share of it used) copy 6 % faster than the eight that fit otherwise, and they leave
     // wave slots on every compute unit, so that another task's workgroups dispatched meanwhile
     // spread evenly instead of piling up on the few compute units that happen to have room.
-    const size_t reserve = g_tuning.copy_lds_reserve < 0 ? 32768 : (size_t)g_tuning.copy_lds_reserve;
+    const size_t reserve = tn.copy_lds_reserve() < 0 ? 32768 : (size_t)tn.copy_lds_reserve();
     const size_t lds_launch = (lds_bytes > reserve ? lds_bytes : reserve);
 #define XS_COPY_LAUNCH(LDS, NT)                                                                   \
     hipLaunchKernelGGL((copy_kernel<UNPACK, DETECT, DT, LDS, NT>), grid, block, lds_launch,        \
@@ -235,28 +235,28 @@ static int launch_copy(const xs_plan *plan, const void *const *tables, void *con
     return XS_OK;
 }
 
-int launch_pack(const xs_plan *plan, const void *const *tables, void *const *buckets,
+int launch_pack(const Tuning &tn, const xs_plan *plan, const void *const *tables, void *const *buckets,
                 uint32_t n_pairs, int32_t *found_inf, hipStream_t stream)
 {
     if (!found_inf)   // a plain copy: only the element size matters
         return plan->elem_size == 4
-                   ? launch_copy<false, false, XS_F32>(plan, tables, buckets, n_pairs, nullptr, stream)
-                   : launch_copy<false, false, XS_F16>(plan, tables, buckets, n_pairs, nullptr, stream);
+                   ? launch_copy<false, false, XS_F32>(tn, plan, tables, buckets, n_pairs, nullptr, stream)
+                   : launch_copy<false, false, XS_F16>(tn, plan, tables, buckets, n_pairs, nullptr, stream);
     switch (plan->dtype) {
-    case XS_F16: return launch_copy<false, true, XS_F16>(plan, tables, buckets, n_pairs, found_inf, stream);
-    case XS_BF16: return launch_copy<false, true, XS_BF16>(plan, tables, buckets, n_pairs, found_inf, stream);
-    default: return launch_copy<false, true, XS_F32>(plan, tables, buckets, n_pairs, found_inf, stream);
+    case XS_F16: return launch_copy<false, true, XS_F16>(tn, plan, tables, buckets, n_pairs, found_inf, stream);
+    case XS_BF16: return launch_copy<false, true, XS_BF16>(tn, plan, tables, buckets, n_pairs, found_inf, stream);
+    default: return launch_copy<false, true, XS_F32>(tn, plan, tables, buckets, n_pairs, found_inf, stream);
     }
 }
 
-int launch_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,
+int launch_unpack(const Tuning &tn, const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,
                   hipStream_t stream)
 {
     const void *table = tensor_ptrs;
     void *b = const_cast<void *>(bucket);
     if (plan->elem_size == 4)
-        return launch_copy<true, false, XS_F32>(plan, &table, &b, 1, nullptr, stream);
-    return launch_copy<true, false, XS_F16>(plan, &table, &b, 1, nullptr, stream);
+        return launch_copy<true, false, XS_F32>(tn, plan, &table, &b, 1, nullptr, stream);
+    return launch_copy<true, false, XS_F16>(tn, plan, &table, &b, 1, nullptr, stream);
 }
 
 }  // namespace xs

@@ -39,6 +39,8 @@ struct xs_app {
     hipEvent_t sync_done;
     bool grads_outstanding;   // grads_ready recorded and not yet consumed by a sync
     bool has_sync;            // sync_done has been recorded at least once
+    bool own_tuning;          // launch settings of its own (xs_app_desc.tuning)
+    xs::Tuning tuning;
 };
 
 using namespace xs;
@@ -68,6 +70,15 @@ extern "C" int xs_app_create(const xs_app_desc *d, xs_app **out)
         return fail(XS_ERR_INVALID_ARG, "xs_app_create: a required pointer is NULL");
     if (!empty && gather && !d->grad_ptrs_tw)
         return fail(XS_ERR_INVALID_ARG, "xs_app_create: XS_APP_FUSED_GATHER needs grad_ptrs_tw");
+    if (gather && d->found_inf)
+        return fail(XS_ERR_UNSUPPORTED,
+                    "xs_app_create: found_inf cannot be honoured with XS_APP_FUSED_GATHER: no pack runs "
+                    "that could raise the flag before the in-place pass");
+    Tuning tuning = {};
+    if (d->tuning) {
+        const int rc = tuning_check(d->tuning, &tuning);
+        if (rc != XS_OK) return rc;
+    }
     if (!empty && !gather && (!d->grad_tensor_ptrs || !d->replica_buckets))
         return fail(XS_ERR_INVALID_ARG, "xs_app_create: a required pointer is NULL");
     if (!empty) {
@@ -104,6 +115,8 @@ extern "C" int xs_app_create(const xs_app_desc *d, xs_app **out)
     a->compute_ctx = d->compute_ctx;
     a->grads_outstanding = false;
     a->has_sync = false;
+    a->own_tuning = d->tuning != nullptr;
+    a->tuning = tuning;
     a->grads_ready = nullptr;
     a->sync_done = nullptr;
     hipError_t e = hipEventCreateWithFlags(&a->grads_ready, hipEventDisableTiming);
@@ -134,28 +147,24 @@ extern "C" int xs_app_destroy(xs_app *a)
 static int enqueue_sync(xs_app *a, hipStream_t s)
 {
     if (a->gplan->bucket_elems == 0) return XS_OK;
-    if (a->flags & XS_APP_FUSED_GATHER) {
-        if (a->tensor_hp)
-            return xs_fused_gather_reduce_sgd_pt(a->gplan, a->gather_table, a->W, a->params,
-                                                 a->momentum, nullptr, nullptr, a->param_table,
-                                                 a->tensor_hp, a->hp.inv_loss_scale, a->found_inf,
-                                                 nullptr, s);
-        return xs_fused_gather_reduce_sgd(a->gplan, a->gather_table, a->W, a->params, a->momentum,
-                                          nullptr, nullptr, a->param_table, &a->hp, a->found_inf, s);
-    }
-    int rc = xs_fuse_pack_many(a->gplan, a->grad_tables.data(), a->buckets.data(), a->W,
-                               a->found_inf, s);
+    const Tuning tn = a->own_tuning ? a->tuning : tuning_now();
+    if (a->flags & XS_APP_FUSED_GATHER)
+        return gather_reduce_sgd_impl(tn, a->gplan, a->gather_table, a->W, a->params, a->momentum,
+                                      nullptr, nullptr, a->param_table, &a->hp, a->tensor_hp,
+                                      nullptr, nullptr, s);
+    int rc = fuse_pack_many_impl(tn, a->gplan, a->grad_tables.data(), a->buckets.data(), a->W,
+                                 a->found_inf, s);
     if (rc != XS_OK) return rc;
     if (a->tensor_hp)
-        rc = xs_fused_reduce_sgd_pt(a->gplan, (const void *const *)a->buckets.data(), a->W, a->params,
-                                    a->momentum, nullptr, nullptr, a->tensor_hp,
-                                    a->hp.inv_loss_scale, a->found_inf, nullptr, s);
+        rc = reduce_sgd_pt_impl(tn, a->gplan, (const void *const *)a->buckets.data(), a->W, a->params,
+                                a->momentum, nullptr, nullptr, a->tensor_hp, a->hp.inv_loss_scale,
+                                a->found_inf, nullptr, s);
     else
-        rc = xs_fused_reduce_sgd((const void *const *)a->buckets.data(), a->W, a->gplan->dtype,
-                                 a->gplan->bucket_elems, a->params, a->momentum, nullptr, nullptr,
-                                 &a->hp, a->found_inf, s);
+        rc = reduce_sgd_impl(tn, nullptr, nullptr, (const void *const *)a->buckets.data(), a->W,
+                             a->gplan->dtype, a->gplan->bucket_elems, a->params, a->momentum, nullptr,
+                             nullptr, &a->hp, a->found_inf, nullptr, s);
     if (rc != XS_OK) return rc;
-    return xs_fuse_unpack(a->pplan, a->params, a->param_table, s);
+    return fuse_unpack_impl(tn, a->pplan, a->params, a->param_table, s);
 }
 
 extern "C" int xs_app_sync(xs_app *a, void *hip_stream)

@@ -14,6 +14,7 @@ typedef __attribute__((address_space(1))) unsigned char gbyte;
 typedef __attribute__((address_space(1))) u32x4 gvec;
 
 constexpr int kWave = 64;
+constexpr int kMaxReduceThreads = 256;   // reduce kernels: 1, 2 or 4 wavefronts per workgroup
 
 // ---- gradient element types ------------------------------------------------------------
 // GT = XS_F32 (0): one element per 32-bit word.  XS_F16 (1) / XS_BF16 (2): two per word.
@@ -190,9 +191,10 @@ __device__ __forceinline__ void store8(u32x2 *p, u32x2 v)
 // 32+(L>>1), same slot.  All 64 lanes must be active.
 __device__ __forceinline__ void exchange_half_row(float (&s)[8])
 {
-    const int src0 = (int)((threadIdx.x >> 1) << 2);
-    const int src1 = (int)((32u + (threadIdx.x >> 1)) << 2);
-    const bool odd = (threadIdx.x & 1u) != 0u;
+    const uint32_t lane = threadIdx.x & 63u;
+    const int src0 = (int)((lane >> 1) << 2);
+    const int src1 = (int)((32u + (lane >> 1)) << 2);
+    const bool odd = (lane & 1u) != 0u;
     float t[8];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {

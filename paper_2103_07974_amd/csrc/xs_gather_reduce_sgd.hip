@@ -94,8 +94,9 @@ __device__ __forceinline__ void vector_path(const GatherArgs &a, uint32_t t, uin
 #pragma unroll
     for (int q = 0; q < SV; ++q) {
         if constexpr (EXCH) {
-            const uint64_t lane_off = (uint64_t)threadIdx.x * VEC;       // j = row start + lane_off
-            const uint64_t d = (uint64_t)q * 4 * kWave + 4 * threadIdx.x;
+            const uint32_t lane = threadIdx.x & (kWave - 1);
+            const uint64_t lane_off = (uint64_t)lane * VEC;               // j = row start + lane_off
+            const uint64_t d = (uint64_t)q * 4 * kWave + 4 * lane;
             sj[q] = j - lane_off + d;
             sk[q] = k - lane_off + d;
         } else {
@@ -164,15 +165,17 @@ __device__ __forceinline__ void element_path(const GatherArgs &a, uint32_t &te, 
 }
 
 template <int W, int GT, bool DETECT, bool VIEWS, bool PT>
-__global__ __launch_bounds__(kWave) void gather_reduce_sgd_kernel(GatherArgs a)
+__global__ __launch_bounds__(kMaxReduceThreads) void gather_reduce_sgd_kernel(GatherArgs a)
 {
     constexpr int VEC = 16 / Grad<GT>::ES;
     constexpr uint64_t ROW = (uint64_t)kWave * VEC;
     if (a.found_inf != nullptr && *(volatile int32_t *)a.found_inf != 0) return;
     bool bad = false;
 
-    for (uint64_t row = blockIdx.x; row < a.n_rows; row += gridDim.x) {
-        const uint64_t j = row * ROW + (uint64_t)threadIdx.x * VEC;    // lane's first bucket element
+    // each wavefront of the workgroup owns one row per trip
+    const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+    for (uint64_t row = (uint64_t)blockIdx.x * waves + wave; row < a.n_rows; row += (uint64_t)gridDim.x * waves) {
+        const uint64_t j = row * ROW + (uint64_t)lane * VEC;           // lane's first bucket element
         if (j >= a.n_bucket) continue;
         const uint32_t t_row = a.tb.row_first[row];
         uint32_t t = t_row;
@@ -207,14 +210,15 @@ __global__ __launch_bounds__(kWave) void gather_reduce_sgd_kernel(GatherArgs a)
 
 // Any W: element by element with a run-time replica count.
 template <int GT, bool DETECT, bool VIEWS, bool PT>
-__global__ __launch_bounds__(kWave) void gather_reduce_sgd_anyw_kernel(GatherArgs a)
+__global__ __launch_bounds__(kMaxReduceThreads) void gather_reduce_sgd_anyw_kernel(GatherArgs a)
 {
     constexpr int VEC = 16 / Grad<GT>::ES;
     constexpr uint64_t ROW = (uint64_t)kWave * VEC;
     if (a.found_inf != nullptr && *(volatile int32_t *)a.found_inf != 0) return;
     bool bad = false;
-    for (uint64_t row = blockIdx.x; row < a.n_rows; row += gridDim.x) {
-        const uint64_t j = row * ROW + (uint64_t)threadIdx.x * VEC;
+    const uint32_t waves = blockDim.x / kWave, wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+    for (uint64_t row = (uint64_t)blockIdx.x * waves + wave; row < a.n_rows; row += (uint64_t)gridDim.x * waves) {
+        const uint64_t j = row * ROW + (uint64_t)lane * VEC;
         if (j >= a.n_bucket) continue;
         uint32_t te = a.tb.row_first[row];
         for (int e = 0; e < VEC; ++e) {
@@ -229,51 +233,51 @@ __global__ __launch_bounds__(kWave) void gather_reduce_sgd_anyw_kernel(GatherArg
 
 // ---- dispatch ---------------------------------------------------------------------------
 template <int W, int GT, bool PT>
-static void launch_g(const GatherArgs &a, bool detect, bool views, dim3 grid, unsigned lds,
+static void launch_g(const GatherArgs &a, bool detect, bool views, dim3 grid, dim3 block, unsigned lds,
                      hipStream_t stream)
 {
     if (detect)
-        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, true, false, PT>), grid, dim3(kWave), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, true, false, PT>), grid, block, lds, stream, a);
     else if (views)
-        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, false, true, PT>), grid, dim3(kWave), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, false, true, PT>), grid, block, lds, stream, a);
     else
-        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, false, false, PT>), grid, dim3(kWave), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_kernel<W, GT, false, false, PT>), grid, block, lds, stream, a);
 }
 
 template <int GT, bool PT>
-static void launch_ganyw(const GatherArgs &a, bool detect, bool views, dim3 grid, unsigned lds,
+static void launch_ganyw(const GatherArgs &a, bool detect, bool views, dim3 grid, dim3 block, unsigned lds,
                          hipStream_t stream)
 {
     if (detect)
-        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, true, false, PT>), grid, dim3(kWave), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, true, false, PT>), grid, block, lds, stream, a);
     else if (views)
-        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, false, true, PT>), grid, dim3(kWave), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, false, true, PT>), grid, block, lds, stream, a);
     else
-        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, false, false, PT>), grid, dim3(kWave), lds, stream, a);
+        hipLaunchKernelGGL((gather_reduce_sgd_anyw_kernel<GT, false, false, PT>), grid, block, lds, stream, a);
 }
 
 template <int GT, bool PT>
-static void launch_w(const GatherArgs &a, bool detect, bool views, dim3 grid, unsigned lds,
+static void launch_w(const GatherArgs &a, bool detect, bool views, dim3 grid, dim3 block, unsigned lds,
                      hipStream_t stream)
 {
     switch (a.W) {
-    case 2: launch_g<2, GT, PT>(a, detect, views, grid, lds, stream); break;
-    case 4: launch_g<4, GT, PT>(a, detect, views, grid, lds, stream); break;
-    case 8: launch_g<8, GT, PT>(a, detect, views, grid, lds, stream); break;
-    case 16: launch_g<16, GT, PT>(a, detect, views, grid, lds, stream); break;
-    default: launch_ganyw<GT, PT>(a, detect, views, grid, lds, stream); break;
+    case 2: launch_g<2, GT, PT>(a, detect, views, grid, block, lds, stream); break;
+    case 4: launch_g<4, GT, PT>(a, detect, views, grid, block, lds, stream); break;
+    case 8: launch_g<8, GT, PT>(a, detect, views, grid, block, lds, stream); break;
+    case 16: launch_g<16, GT, PT>(a, detect, views, grid, block, lds, stream); break;
+    default: launch_ganyw<GT, PT>(a, detect, views, grid, block, lds, stream); break;
     }
 }
 
 template <int GT>
-static void launch_gt(const GatherArgs &a, bool detect, bool views, dim3 grid, unsigned lds,
+static void launch_gt(const GatherArgs &a, bool detect, bool views, dim3 grid, dim3 block, unsigned lds,
                       hipStream_t stream)
 {
-    if (a.tensor_hp != nullptr) launch_w<GT, true>(a, detect, views, grid, lds, stream);
-    else launch_w<GT, false>(a, detect, views, grid, lds, stream);
+    if (a.tensor_hp != nullptr) launch_w<GT, true>(a, detect, views, grid, block, lds, stream);
+    else launch_w<GT, false>(a, detect, views, grid, block, lds, stream);
 }
 
-int launch_gather_reduce_sgd(const xs_plan *plan, const void *const *grad_ptrs, uint32_t W,
+int launch_gather_reduce_sgd(const Tuning &tn, const xs_plan *plan, const void *const *grad_ptrs, uint32_t W,
                              const float *x_in, const float *v_in, float *x_out, float *v_out,
                              void *const *param_ptrs, int view_dtype, const xs_sgd_hparams &hp,
                              const xs_tensor_hparams *tensor_hp, int32_t *found_inf, bool detect,
@@ -298,25 +302,26 @@ int launch_gather_reduce_sgd(const xs_plan *plan, const void *const *grad_ptrs, 
     a.tensor_hp = (const f32x4 *)tensor_hp;
     a.found_inf = found_inf;
 
-    uint64_t blocks = plan->n_rows;
-    if (g_tuning.reduce_wg_per_cu > 0) {
-        const uint64_t cap = (uint64_t)cus * (uint64_t)g_tuning.reduce_wg_per_cu;
+    const uint64_t waves = (uint64_t)tn.reduce_waves_per_wg();
+    uint64_t blocks = (plan->n_rows + waves - 1) / waves;
+    if (tn.reduce_wg_per_cu() > 0) {
+        const uint64_t cap = (uint64_t)cus * (uint64_t)tn.reduce_wg_per_cu();
         if (blocks > cap) blocks = cap;
     }
-    if (g_tuning.reduce_max_wg > 0 && blocks > (uint64_t)g_tuning.reduce_max_wg)
-        blocks = (uint64_t)g_tuning.reduce_max_wg;
+    if (tn.reduce_max_wg() > 0 && blocks > (uint64_t)tn.reduce_max_wg())
+        blocks = (uint64_t)tn.reduce_max_wg();
     if (blocks > 0x7fffffffull) blocks = 0x7fffffffull;
-    const dim3 grid((unsigned)blocks);
+    const dim3 grid((unsigned)blocks), block((unsigned)(waves * kWave));
     // the address look-ups in front of the loads want about twice the residency of the
     // bucket form: 20 one-wave workgroups per compute unit for fp32, 10 for half precision
     const int lds_auto = half ? 16384 : 8192;
-    const unsigned lds = (unsigned)(g_tuning.gather_lds_reserve < 0 ? lds_auto : g_tuning.gather_lds_reserve);
+    const unsigned lds = (unsigned)(tn.gather_lds_reserve() < 0 ? lds_auto : tn.gather_lds_reserve());
     const bool views = param_ptrs != nullptr;
 
     switch (plan->dtype) {
-    case XS_F16: launch_gt<XS_F16>(a, detect, views, grid, lds, stream); break;
-    case XS_BF16: launch_gt<XS_BF16>(a, detect, views, grid, lds, stream); break;
-    default: launch_gt<XS_F32>(a, detect, views, grid, lds, stream); break;
+    case XS_F16: launch_gt<XS_F16>(a, detect, views, grid, block, lds, stream); break;
+    case XS_BF16: launch_gt<XS_BF16>(a, detect, views, grid, block, lds, stream); break;
+    default: launch_gt<XS_F32>(a, detect, views, grid, block, lds, stream); break;
     }
     XS_HIP_TRY(hipGetLastError());
     return XS_OK;

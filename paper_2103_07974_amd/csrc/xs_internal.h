@@ -25,19 +25,26 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 int compute_units();   // > 0, or a negative xs_status
 
 // ---- tuning ---------------------------------------------------------------------
-struct Tuning {              // indexed by xs_tuning_key
-    int reduce_wg_per_cu;     // 0: one vector per lane, no loop
-    int copy_wg_per_cu;       // 0: one work item per workgroup (a few for large LDS tables)
-    int nt_grads;             // non-temporal loads of gradient replicas
-    int nt_state;             // non-temporal loads and stores of parameters and momentum
-    int reduce_lds_reserve;   // bytes of LDS reserved per reduce workgroup (-1: per dtype)
-    int reduce_max_wg;        // absolute cap on reduce workgroups (0 = none): background pacing
-    int copy_max_wg;          // absolute cap on pack/unpack workgroups (0 = none)
-    int copy_nt;              // non-temporal loads and stores in pack/unpack
-    int gather_lds_reserve;   // as reduce_lds_reserve, for the gathering form
-    int copy_lds_reserve;     // LDS reserved per pack/unpack workgroup beyond its table (-1: default)
+// One launch's settings, indexed by xs_tuning_key.  The process-wide defaults live in
+// relaxed atomics (xs_tuning_set may run while another thread launches); every entry point
+// takes one snapshot and hands it down, and an xs_app may carry its own copy instead.
+struct Tuning {
+    int v[XS_TUNE_COUNT];
+    int reduce_wg_per_cu() const { return v[XS_TUNE_REDUCE_WG_PER_CU]; }      // 0: one vector per lane, no loop
+    int copy_wg_per_cu() const { return v[XS_TUNE_COPY_WG_PER_CU]; }          // 0: one work item per workgroup
+    bool nt_grads() const { return v[XS_TUNE_NT_GRADS] != 0; }
+    bool nt_state() const { return v[XS_TUNE_NT_STATE] != 0; }
+    int reduce_lds_reserve() const { return v[XS_TUNE_REDUCE_LDS_RESERVE]; }  // -1: per dtype
+    int reduce_max_wg() const { return v[XS_TUNE_REDUCE_MAX_WG]; }
+    int copy_max_wg() const { return v[XS_TUNE_COPY_MAX_WG]; }
+    bool copy_nt() const { return v[XS_TUNE_COPY_NT] != 0; }
+    int gather_lds_reserve() const { return v[XS_TUNE_GATHER_LDS_RESERVE]; }
+    int copy_lds_reserve() const { return v[XS_TUNE_COPY_LDS_RESERVE]; }
+    int reduce_waves_per_wg() const { return v[XS_TUNE_REDUCE_WAVES_PER_WG]; }
+    bool reduce_small() const { return v[XS_TUNE_REDUCE_SMALL] != 0; }
 };
-extern Tuning g_tuning;
+Tuning tuning_now();                                   // snapshot of the process-wide settings
+int tuning_check(const int32_t *values, Tuning *out);  // XS_OK, or which value is out of range
 
 // ---- plan -------------------------------------------------------------------------
 // Copy work is cut into chunks of kChunkBytes of one tensor's bucket segment
@@ -79,21 +86,45 @@ constexpr uint32_t XS_APP_MAGIC = 0x78734131u;   // "xsA1"
 
 namespace xs {
 // launchers implemented next to their kernels
-int launch_pack(const xs_plan *plan, const void *const *tables /* host array of device tables */,
+int launch_pack(const Tuning &tn, const xs_plan *plan,
+                const void *const *tables /* host array of device tables */,
                 void *const *buckets /* host array */, uint32_t n_pairs, int32_t *found_inf,
                 hipStream_t stream);
-int launch_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,
+int launch_unpack(const Tuning &tn, const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,
                   hipStream_t stream);
-int launch_gather_reduce_sgd(const xs_plan *plan, const void *const *grad_ptrs, uint32_t W,
+int launch_gather_reduce_sgd(const Tuning &tn, const xs_plan *plan, const void *const *grad_ptrs, uint32_t W,
                              const float *x_in, const float *v_in, float *x_out, float *v_out,
                              void *const *param_ptrs, int view_dtype, const xs_sgd_hparams &hp,
                              const xs_tensor_hparams *tensor_hp, int32_t *found_inf, bool detect,
                              hipStream_t stream);
-int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64_t n,
+int launch_reduce_sgd(const Tuning &tn, const void *const *replicas, uint32_t W, int dtype, uint64_t n,
                       const float *x_in, const float *v_in, float *x_out, float *v_out,
                       const xs_sgd_hparams &hp, int32_t *found_inf, bool detect,
                       void *model_copy, int model_copy_dtype, const xs_plan *plan,
                       const xs_tensor_hparams *tensor_hp, hipStream_t stream);
 // plan + tensor_hp (both or neither): one (lr, momentum, weight decay) record per tensor of
 // the plan replaces hp's three; hp.inv_loss_scale always applies.
+
+// The entry points' argument checks + launch under explicit launch settings (the extern "C"
+// functions pass tuning_now(); an xs_app passes its own settings if it has any).
+int fuse_pack_many_impl(const Tuning &tn, const xs_plan *plan,
+                        const void *const *const *tensor_ptr_tables, void *const *buckets, uint32_t n,
+                        int32_t *found_inf, hipStream_t stream);
+int fuse_unpack_impl(const Tuning &tn, const xs_plan *plan, const void *bucket,
+                     void *const *tensor_ptrs, hipStream_t stream);
+int reduce_sgd_impl(const Tuning &tn, const xs_plan *plan, const xs_tensor_hparams *tensor_hp,
+                    const void *const *replica_buckets, uint32_t W, int grad_dtype, uint64_t n_elems,
+                    float *params, float *momentum, float *params_out, float *momentum_out,
+                    const xs_sgd_hparams *hp, int32_t *found_inf, const xs_mp_options *mp,
+                    hipStream_t stream);
+int reduce_sgd_pt_impl(const Tuning &tn, const xs_plan *gradient_plan,
+                       const void *const *replica_buckets, uint32_t W, float *params, float *momentum,
+                       float *params_out, float *momentum_out, const xs_tensor_hparams *tensor_hp,
+                       float inv_loss_scale, int32_t *found_inf, const xs_mp_options *mp,
+                       hipStream_t stream);
+int gather_reduce_sgd_impl(const Tuning &tn, const xs_plan *gradient_plan, const void *const *grad_ptrs,
+                           uint32_t W, float *params, float *momentum, float *params_out,
+                           float *momentum_out, void *const *param_tensor_ptrs,
+                           const xs_sgd_hparams *hp, const xs_tensor_hparams *tensor_hp,
+                           int32_t *found_inf, const xs_mp_options *mp, hipStream_t stream);
 }  // namespace xs

@@ -10,7 +10,10 @@
 //    every operation rounded to fp32 separately (-ffp-contract=off): bit-reproducible.
 //  * One-wavefront workgroups, one vector per lane, no loop in the default launch: workgroups
 //    are dispatched in address order as earlier ones retire, which keeps the DRAM access
-//    front tight (a strided persistent grid measured 25 % slower on MI355X).
+//    front tight (a strided persistent grid measured 25 % slower on MI355X).  A launch may
+//    ask for 2 or 4 wavefronts per workgroup instead (each wavefront still owns one row of
+//    64 vectors): a 4-wave workgroup puts one wavefront on every SIMD of its compute unit,
+//    which is how a synchronisation shares the compute units with another task's kernels.
 //  * The launch reserves LDS the kernel never touches, to cap how many wavefronts share a
 //    compute unit: about 100-120 KB of loads in flight per compute unit is the optimum.
 //  * Every stream is touched once, so loads and stores carry the non-temporal hint.
@@ -23,7 +26,7 @@
 
 namespace xs {
 
-constexpr int kThreads = kWave;   // one wavefront per workgroup: finest dispatch grain
+constexpr int kThreads = kWave;   // one row = one wavefront = 64 gradient vectors
 
 template <int N>
 struct ReplicaPtrs {
@@ -101,7 +104,7 @@ __device__ __forceinline__ RowHp row_hp(const TensorHp &h, uint64_t first_vec, u
 // VEC elements per lane per trip: 4 (fp32 gradients) or 8 (fp16 / bf16 gradients), so that
 // every gradient load is 16 bytes wide.
 template <int W, int GT, bool DETECT, bool NTG, bool NTS, bool PT>
-__global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(ReplicaPtrs<W> reps, ReduceArgs a)
+__global__ __launch_bounds__(kMaxReduceThreads) void reduce_sgd_kernel(ReplicaPtrs<W> reps, ReduceArgs a)
 {
     constexpr bool HALF = Grad<GT>::HALF;
     constexpr int VEC = 16 / Grad<GT>::ES;
@@ -109,10 +112,11 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(ReplicaPtrs<W> rep
     if (a.found_inf != nullptr && *(volatile int32_t *)a.found_inf != 0) return;
 
     const uint64_t nvec = a.n / VEC;
-    const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    const uint32_t lane = threadIdx.x & (kThreads - 1);
     bool bad = false;
 
-    for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
         u32x4 g[W];
 #pragma unroll
         for (int w = 0; w < W; ++w) g[w] = load16<NTG>((const u32x4 *)reps.p[w] + i);
@@ -125,10 +129,10 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(ReplicaPtrs<W> rep
         uint64_t sx[SV];
         bool exchanged = false;
         if constexpr (HALF) {
-            const uint64_t row0 = i - threadIdx.x;                 // vector index of lane 0
+            const uint64_t row0 = i - lane;                        // vector index of lane 0
             exchanged = row0 + (kThreads - 1) < nvec;              // uniform: the whole row is live
-            sx[0] = exchanged ? row0 * 2 + threadIdx.x : i * 2;
-            sx[1] = exchanged ? row0 * 2 + kThreads + threadIdx.x : i * 2 + 1;
+            sx[0] = exchanged ? row0 * 2 + lane : i * 2;
+            sx[1] = exchanged ? row0 * 2 + kThreads + lane : i * 2 + 1;
         } else {
             sx[0] = i;
         }
@@ -139,7 +143,7 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(ReplicaPtrs<W> rep
             v[k] = load16f<NTS>((const f32x4 *)a.v_in + sx[k]);
         }
         RowHp rh;
-        if constexpr (PT) rh = row_hp<VEC>(a.thp, i - threadIdx.x, a.n);
+        if constexpr (PT) rh = row_hp<VEC>(a.thp, i - lane, a.n);
         else rh.rec = f32x4{a.lr, a.mu, a.wd, 0.f};
         float s[VEC];
 #pragma unroll
@@ -172,7 +176,7 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(ReplicaPtrs<W> rep
 // Any W up to XS_MAX_REPLICAS: replica loop with a run-time trip count, four loads in flight
 // at a time.  Same arithmetic and order as the specialised kernels; plain lane mapping.
 template <int GT, bool DETECT, bool PT>
-__global__ __launch_bounds__(kThreads) void reduce_sgd_anyw_kernel(
+__global__ __launch_bounds__(kMaxReduceThreads) void reduce_sgd_anyw_kernel(
     ReplicaPtrs<XS_MAX_REPLICAS> reps, uint32_t W, ReduceArgs a)
 {
     constexpr int ES = Grad<GT>::ES;
@@ -180,11 +184,12 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_anyw_kernel(
     constexpr int SV = VEC / 4;
     if (a.found_inf != nullptr && *(volatile int32_t *)a.found_inf != 0) return;
     const uint64_t nvec = a.n / VEC;
-    const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    const uint32_t lane = threadIdx.x & (kThreads - 1);
     bool bad = false;
-    for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
         RowHp rh;
-        if constexpr (PT) rh = row_hp<VEC>(a.thp, i - threadIdx.x, a.n);
+        if constexpr (PT) rh = row_hp<VEC>(a.thp, i - lane, a.n);
         else rh.rec = f32x4{a.lr, a.mu, a.wd, 0.f};
         float s[VEC];
         accumulate<GT, DETECT>(*((const u32x4 *)reps.p[0] + i), true, s, bad);
@@ -214,7 +219,7 @@ __global__ __launch_bounds__(kThreads) void reduce_sgd_anyw_kernel(
 struct Launch {
     const void *const *replicas;
     ReduceArgs a;
-    dim3 grid;
+    dim3 grid, block;
     unsigned lds_reserve;
     hipStream_t stream;
 };
@@ -224,7 +229,7 @@ static void launch_one(const Launch &l)
 {
     ReplicaPtrs<W> r;
     for (int w = 0; w < W; ++w) r.p[w] = l.replicas[w];
-    hipLaunchKernelGGL((reduce_sgd_kernel<W, GT, DETECT, NTG, NTS, PT>), l.grid, dim3(kThreads),
+    hipLaunchKernelGGL((reduce_sgd_kernel<W, GT, DETECT, NTG, NTS, PT>), l.grid, l.block,
                        l.lds_reserve, l.stream, r, l.a);
 }
 
@@ -264,7 +269,7 @@ static void launch_anyw_one(const Launch &l, uint32_t W)
 {
     ReplicaPtrs<XS_MAX_REPLICAS> r;
     for (uint32_t w = 0; w < XS_MAX_REPLICAS; ++w) r.p[w] = w < W ? l.replicas[w] : nullptr;
-    hipLaunchKernelGGL((reduce_sgd_anyw_kernel<GT, DETECT, PT>), l.grid, dim3(kThreads), l.lds_reserve,
+    hipLaunchKernelGGL((reduce_sgd_anyw_kernel<GT, DETECT, PT>), l.grid, l.block, l.lds_reserve,
                        l.stream, r, W, l.a);
 }
 
@@ -276,7 +281,7 @@ static void launch_anyw(const Launch &l, uint32_t W, bool detect)
     else        { if (pt) launch_anyw_one<GT, false, true>(l, W); else launch_anyw_one<GT, false, false>(l, W); }
 }
 
-int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64_t n,
+int launch_reduce_sgd(const Tuning &tn, const void *const *replicas, uint32_t W, int dtype, uint64_t n,
                       const float *x_in, const float *v_in, float *x_out, float *v_out,
                       const xs_sgd_hparams &hp, int32_t *found_inf, bool detect,
                       void *model_copy, int model_copy_dtype, const xs_plan *plan,
@@ -286,14 +291,15 @@ int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64
     if (cus < 0) return cus;
     const bool half = dtype != XS_F32;
     const uint64_t vec = half ? 8 : 4;
-    uint64_t blocks = (n / vec + kThreads - 1) / kThreads;
+    const uint64_t threads = (uint64_t)kThreads * (uint64_t)tn.reduce_waves_per_wg();
+    uint64_t blocks = (n / vec + threads - 1) / threads;
     if (blocks == 0) blocks = 1;   // tail only
-    if (g_tuning.reduce_wg_per_cu > 0) {
-        const uint64_t cap = (uint64_t)cus * (uint64_t)g_tuning.reduce_wg_per_cu;
+    if (tn.reduce_wg_per_cu() > 0) {
+        const uint64_t cap = (uint64_t)cus * (uint64_t)tn.reduce_wg_per_cu();
         if (blocks > cap) blocks = cap;
     }
-    if (g_tuning.reduce_max_wg > 0 && blocks > (uint64_t)g_tuning.reduce_max_wg)
-        blocks = (uint64_t)g_tuning.reduce_max_wg;
+    if (tn.reduce_max_wg() > 0 && blocks > (uint64_t)tn.reduce_max_wg())
+        blocks = (uint64_t)tn.reduce_max_wg();
     if (blocks > 0x7fffffffull) blocks = 0x7fffffffull;   // the loop covers the rest
 
     Launch l;
@@ -313,6 +319,7 @@ int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64
     l.a.thp.row_first = plan ? plan->tables.row_first : nullptr;
     l.a.thp.n_tensors = plan ? plan->n_tensors : 0;
     l.grid = dim3((unsigned)blocks);
+    l.block = dim3((unsigned)threads);
     l.stream = stream;
     // Measured on MI355X: the pass is fastest with 10 one-wave workgroups per compute unit
     // (fp32 W = 8: 12 loads per lane, about 120 KB in flight per compute unit; fp16 W = 16:
@@ -320,10 +327,10 @@ int launch_reduce_sgd(const void *const *replicas, uint32_t W, int dtype, uint64
     // fewer expose the latency of the kernel's prologue.  The LDS reservation (unused by the
     // kernel) is what caps the residency.
     const int lds_auto = 16384;
-    l.lds_reserve = (unsigned)(g_tuning.reduce_lds_reserve < 0 ? lds_auto : g_tuning.reduce_lds_reserve);
-    const bool ntg = g_tuning.nt_grads != 0, nts = g_tuning.nt_state != 0;
+    l.lds_reserve = (unsigned)(tn.reduce_lds_reserve() < 0 ? lds_auto : tn.reduce_lds_reserve());
+    const bool ntg = tn.nt_grads(), nts = tn.nt_state();
 
-    switch (W) {
+    switch (tn.reduce_small() ? 0u : W) {
     case 2: launch_w<2>(l, dtype, detect, ntg, nts); break;
     case 4: launch_w<4>(l, dtype, detect, ntg, nts); break;
     case 8: launch_w<8>(l, dtype, detect, ntg, nts); break;

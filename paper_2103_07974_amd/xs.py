@@ -41,7 +41,12 @@ TUNE_COPY_MAX_WG = 6
 TUNE_COPY_NT = 7
 TUNE_GATHER_LDS_RESERVE = 8
 TUNE_COPY_LDS_RESERVE = 9
-N_TUNING_KEYS = 10
+TUNE_REDUCE_WAVES_PER_WG = 10
+TUNE_REDUCE_SMALL = 11
+N_TUNING_KEYS = 12
+
+PRESET_ALONE = 0
+PRESET_BESIDE_COMPUTE = 1
 
 EXPORTS = [
     "xs_status_string", "xs_last_error", "xs_bucket_layout", "xs_plan_create", "xs_plan_destroy",
@@ -50,7 +55,8 @@ EXPORTS = [
     "xs_fused_reduce_sgd", "xs_fused_reduce_sgd_mp", "xs_fused_gather_reduce_sgd",
     "xs_fused_gather_reduce_sgd_mp", "xs_fused_reduce_sgd_pt", "xs_fused_gather_reduce_sgd_pt",
     "xs_app_create", "xs_app_destroy", "xs_app_sync", "xs_crossover_step",
-    "xs_crossover_drain", "xs_crossover_iteration", "xs_crossover_finish", "xs_app_wait_sync", "xs_tuning_set", "xs_tuning_get", "xs_standin_alu",
+    "xs_crossover_drain", "xs_crossover_iteration", "xs_crossover_finish", "xs_app_wait_sync",
+    "xs_tuning_set", "xs_tuning_get", "xs_tuning_preset",
 ]
 
 
@@ -83,7 +89,7 @@ class AppDesc(ctypes.Structure):
                 ("hp", SgdHparams), ("found_inf", ctypes.c_void_p),
                 ("compute", COMPUTE_FN), ("compute_ctx", ctypes.c_void_p),
                 ("flags", ctypes.c_uint32), ("grad_ptrs_tw", ctypes.c_void_p),
-                ("tensor_hp", ctypes.c_void_p)]
+                ("tensor_hp", ctypes.c_void_p), ("tuning", ctypes.POINTER(ctypes.c_int32))]
 
 
 XS_APP_FUSED_GATHER = 1
@@ -137,7 +143,7 @@ def lib() -> ctypes.CDLL:
     L.xs_app_wait_sync.argtypes = [vp, vp]
     L.xs_crossover_iteration.argtypes = [ctypes.POINTER(vp), ctypes.c_uint32, vp, vp]
     L.xs_crossover_finish.argtypes = [ctypes.POINTER(vp), ctypes.c_uint32, vp]
-    L.xs_standin_alu.argtypes = [ctypes.c_uint32, ctypes.c_uint32, vp, vp]
+    L.xs_tuning_preset.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int32)]
     L.xs_tuning_set.argtypes = [ctypes.c_int, ctypes.c_int]
     L.xs_tuning_get.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
     for name in EXPORTS:
@@ -381,10 +387,13 @@ class App:
                  lr: float, mu: float, wd: float, inv_loss_scale: float = 1.0,
                  found_inf: Optional[torch.Tensor] = None, compute=None,
                  gather_table: Optional[torch.Tensor] = None, W: Optional[int] = None,
-                 tensor_hp: Optional[torch.Tensor] = None):
+                 tensor_hp: Optional[torch.Tensor] = None,
+                 tuning: Optional[Sequence[int]] = None):
         """With gather_table (device [tensor][worker] addresses) the app synchronises with the
         gathering kernel; grad_tables and replica_buckets may then be empty and W must be given.
-        tensor_hp (device table from tensor_hparams_table) replaces lr/mu/wd per tensor."""
+        tensor_hp (device table from tensor_hparams_table) replaces lr/mu/wd per tensor.
+        tuning (N_TUNING_KEYS launch settings, e.g. from tuning_preset) applies to this app's
+        synchronisations only."""
         W = len(replica_buckets) if W is None else W
         self._keep = (gradient_plan, parameter_plan, list(grad_tables), list(replica_buckets),
                       params, momentum, param_table, found_inf, gather_table, tensor_hp)
@@ -412,6 +421,11 @@ class App:
         d.flags = XS_APP_FUSED_GATHER if gather_table is not None else 0
         d.grad_ptrs_tw = _dptr(gather_table)
         d.tensor_hp = _dptr(tensor_hp)
+        if tuning is not None:
+            if len(tuning) != N_TUNING_KEYS:
+                raise ValueError(f"tuning must have {N_TUNING_KEYS} values")
+            self._tuning = (ctypes.c_int32 * N_TUNING_KEYS)(*[int(v) for v in tuning])
+            d.tuning = ctypes.cast(self._tuning, ctypes.POINTER(ctypes.c_int32))
         h = ctypes.c_void_p()
         _check(lib().xs_app_create(ctypes.byref(d), ctypes.byref(h)), "xs_app_create")
         self.handle = h
@@ -460,9 +474,11 @@ def crossover_finish(apps: Sequence[App], sync_stream) -> None:
            "xs_crossover_finish")
 
 
-def standin_alu(workgroups: int, iters: int, sink: torch.Tensor, stream=None) -> None:
-    _check(lib().xs_standin_alu(int(workgroups), int(iters), _dptr(sink), _stream_ptr(stream)),
-           "xs_standin_alu")
+def tuning_preset(preset: int) -> List[int]:
+    """Launch settings of a named preset (PRESET_ALONE, PRESET_BESIDE_COMPUTE) for App(tuning=...)."""
+    out = (ctypes.c_int32 * N_TUNING_KEYS)()
+    _check(lib().xs_tuning_preset(int(preset), out), "xs_tuning_preset")
+    return list(out)
 
 
 def tuning_set(key: int, value: int) -> None:

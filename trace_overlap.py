@@ -1,12 +1,12 @@
 """Stream-overlap fraction from a rocprofv3 kernel trace (CSV).
 
-    python -m paper_2103_07974_amd.trace_overlap <prefix>_kernel_trace.csv
+    python trace_overlap.py <prefix>_kernel_trace.csv
 
 For the crossover schedule (arXiv 2103.07974, Section 2.1) the question is how much of the
 time the synchronisation kernels run falls inside the time the other task's compute kernels
 run:  sum |sync interval ∩ union(compute intervals)| / sum |sync interval|.
-Kernels of this library (namespace xs::, except the compute stand-in) count as
-synchronisation; GEMM kernels (names starting with Cijk_) and the stand-in count as compute.
+Kernels of libxs.so (namespace xs::) count as synchronisation; GEMM kernels (names starting
+with Cijk_) and the arithmetic-only stand-in of bench_standin.hip count as compute.
 Only the part of the trace where both kinds appear within one millisecond of each other is
 used, so that stand-alone timing loops in the same trace do not dilute the figure.
 """
@@ -18,7 +18,7 @@ from typing import List, Tuple
 
 
 def classify(name: str) -> str | None:
-    if "standin_alu" in name or name.startswith("Cijk_"):
+    if "alu_kernel" in name or name.startswith("Cijk_"):
         return "compute"
     if "xs::" in name:
         return "sync"
