@@ -113,6 +113,24 @@ int xs_fuse_pack(const xs_plan *plan, const void *const *tensor_ptrs, void *buck
 int xs_fuse_pack_many(const xs_plan *plan, const void *const *const *tensor_ptr_tables,
                       void *const *buckets, uint32_t n, int32_t *found_inf, void *hip_stream);
 
+/* xs_fuse_pack for callers that cannot allocate device memory or create a plan first: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Takes the
+ * layout as xs_plan_create does (numel, offsets: host arrays read during the call) and
+ * everything else as xs_fuse_pack does.  The device tables that a plan would own are
+ * rewritten, on hip_stream and in front of the pack, inside a fixed device array of the
+ * library (about 41 KiB per GPU, held until the process ends) by small kernels that carry the
+ * entries in their arguments; the call allocates nothing and copies nothing from host memory.
+ *   - n_tensors > XS_STATIC_MAX_TENSORS returns XS_ERR_SIZE.
+ *   - Every call on a GPU uses that GPU's one array: calls on one stream are ordered and
+ *     correct; calls that may overlap in time on one GPU (different streams or threads) race
+ *     on the tables and must be serialised by the caller.
+ *   - The first call on a device resolves the array's address (a host-side lookup).
+ */
+#define XS_STATIC_MAX_TENSORS 2048
+int xs_fuse_pack_static(const uint64_t *numel, const uint64_t *offsets, uint32_t n_tensors,
+                        int dtype, const void *const *tensor_ptrs, void *bucket,
+                        int32_t *found_inf, void *hip_stream);
+
 /* Unpack: inverse of pack.  Copies each tensor's range of the bucket to
  * tensor_ptrs[t]; padding is ignored.  Same pointer conventions as pack. */
 int xs_fuse_unpack(const xs_plan *plan, const void *bucket, void *const *tensor_ptrs,

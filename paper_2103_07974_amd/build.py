@@ -11,7 +11,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libxs.so")
 OBJ = os.path.join(PKG, "_build")
 SOURCES = ["xs_api.hip", "xs_reduce_sgd.hip", "xs_gather_reduce_sgd.hip", "xs_copy.hip",
-           "xs_crossover.hip"]
+           "xs_crossover.hip", "xs_static.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -50,7 +50,7 @@ PRESET_BESIDE_COMPUTE = 1
 
 EXPORTS = [
     "xs_status_string", "xs_last_error", "xs_bucket_layout", "xs_plan_create", "xs_plan_destroy",
-    "xs_plan_bucket_elems", "xs_plan_n_tensors", "xs_fuse_pack", "xs_fuse_pack_many",
+    "xs_plan_bucket_elems", "xs_plan_n_tensors", "xs_fuse_pack", "xs_fuse_pack_many", "xs_fuse_pack_static",
     "xs_fuse_unpack",
     "xs_fused_reduce_sgd", "xs_fused_reduce_sgd_mp", "xs_fused_gather_reduce_sgd",
     "xs_fused_gather_reduce_sgd_mp", "xs_fused_reduce_sgd_pt", "xs_fused_gather_reduce_sgd_pt",
@@ -118,6 +118,7 @@ def lib() -> ctypes.CDLL:
     L.xs_plan_n_tensors.argtypes = [vp]; L.xs_plan_n_tensors.restype = ctypes.c_uint32
     L.xs_fuse_pack.argtypes = [vp, vp, vp, vp, vp]
     L.xs_fuse_pack_many.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_uint32, vp, vp]
+    L.xs_fuse_pack_static.argtypes = [u64p, u64p, ctypes.c_uint32, ctypes.c_int, vp, vp, vp, vp]
     L.xs_fuse_unpack.argtypes = [vp, vp, vp, vp]
     L.xs_fused_reduce_sgd.argtypes = [ctypes.POINTER(vp), ctypes.c_uint32, ctypes.c_int,
                                       ctypes.c_uint64, vp, vp, vp, vp,
@@ -260,6 +261,21 @@ def fuse_pack_many(plan: Plan, tensor_ptr_tables: Sequence[torch.Tensor],
     bks = (ctypes.c_void_p * max(n, 1))(*[_dptr(b) for b in buckets])
     _check(lib().xs_fuse_pack_many(plan.handle, tabs, bks, n, _dptr(found_inf), _stream_ptr(stream)),
            "xs_fuse_pack_many")
+
+
+STATIC_MAX_TENSORS = 2048
+
+
+def fuse_pack_static(numel: Sequence[int], offsets: Sequence[int], dtype: torch.dtype,
+                     tensor_ptrs: torch.Tensor, bucket: torch.Tensor,
+                     found_inf: Optional[torch.Tensor] = None, stream=None) -> None:
+    """xs_fuse_pack without a plan and without any allocation (layout tables in the library's
+    fixed device array)."""
+    n = len(numel)
+    a = (ctypes.c_uint64 * max(n, 1))(*numel)
+    o = (ctypes.c_uint64 * (n + 1))(*offsets)
+    _check(lib().xs_fuse_pack_static(a, o, n, dtype_code(dtype), _dptr(tensor_ptrs), _dptr(bucket),
+                                     _dptr(found_inf), _stream_ptr(stream)), "xs_fuse_pack_static")
 
 
 def fuse_unpack(plan: Plan, bucket: torch.Tensor, tensor_ptrs: torch.Tensor, stream=None) -> None:
