@@ -268,6 +268,30 @@ int xs_fused_gather_reduce_sgd_pt(const xs_plan *gradient_plan, const void *cons
                                   int32_t *found_inf, const xs_mp_options *mp, void *hip_stream);
 
 /* ------------------------------------------------------------------------
+ * xs_fused_reduce_sgd (in place) with the unpack fused in: the updated parameters are also
+ * written to the per-layer tensors in the same pass, which saves the separate unpack's read
+ * of the parameter bucket (Section 2.1 fuses the tensors so that they can be sent; the way
+ * back to the layers needs no pass of its own).  The replica buckets, params and momentum
+ * have the layout of gradient_plan, whose dtype is the gradients'.
+ *   param_tensor_ptrs  device array of xs_plan_n_tensors() device pointers to the per-layer
+ *                      parameter tensors (element-aligned); element type fp32, or
+ *                      mp->view_dtype (XS_F16 / XS_BF16: half-precision model weights
+ *                      rounded to nearest even from the fp32 master update)
+ *   hp                 lr / momentum / weight_decay for the whole bucket when tensor_hp is
+ *                      NULL; inv_loss_scale always
+ *   tensor_hp          device, one record per tensor, or NULL (see xs_tensor_hparams below)
+ *   found_inf          as in the in-place xs_fused_reduce_sgd: if raised when the kernel
+ *                      starts nothing is written, the views keep the unchanged parameters
+ *   mp                 may be NULL; mp->model_copy is honoured as in xs_fused_reduce_sgd_mp
+ * Bit-identical to xs_fused_reduce_sgd(_pt) followed by xs_fuse_unpack.
+ */
+int xs_fused_reduce_sgd_unpack(const xs_plan *gradient_plan, const void *const *replica_buckets,
+                               uint32_t W, float *params, float *momentum,
+                               void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
+                               const xs_tensor_hparams *tensor_hp, int32_t *found_inf,
+                               const xs_mp_options *mp, void *hip_stream);
+
+/* ------------------------------------------------------------------------
  * Launch settings.  xs_tuning_set changes the process-wide values that every call outside an
  * xs_app reads (one consistent snapshot per call; setting a value while another thread
  * launches is safe, that launch sees the old or the new value).  A task that must be
@@ -359,6 +383,10 @@ typedef struct {
  * form, so nothing could raise found_inf before the in-place pass: xs_app_create returns
  * XS_ERR_UNSUPPORTED when found_inf is given together with this flag. */
 #define XS_APP_FUSED_GATHER 1u
+
+/* Synchronise with W packs (one launch) + xs_fused_reduce_sgd_unpack: the buckets exist, as
+ * they must where the fused tensor is what gets sent, but the unpack has no pass of its own. */
+#define XS_APP_FUSED_UNPACK 2u
 
 /* xs_app_desc.found_inf - loss-scale overflow inside the scheduler (beyond the paper).
  * The W packs of a synchronisation raise the flag when any gradient element of any worker is

@@ -375,9 +375,15 @@ int xs::reduce_sgd_impl(const Tuning &tn, const xs_plan *plan, const xs_tensor_h
                         uint64_t n_elems, float *params, float *momentum,
                         float *params_out, float *momentum_out,
                         const xs_sgd_hparams *hp, int32_t *found_inf,
-                        const xs_mp_options *mp, hipStream_t stream)
+                        const xs_mp_options *mp, void *const *param_tensor_ptrs, hipStream_t stream)
 {
     void *model_copy = mp ? mp->model_copy : nullptr;
+    const int view_dtype = (mp && param_tensor_ptrs) ? mp->view_dtype : XS_F32;
+    if (view_dtype != XS_F32 && !is_half_dtype(view_dtype))
+        return fail(XS_ERR_UNSUPPORTED, "xs_fused_reduce_sgd: unknown view_dtype %d", view_dtype);
+    if (param_tensor_ptrs && (!plan || params_out || momentum_out))
+        return fail(XS_ERR_UNSUPPORTED,
+                    "xs_fused_reduce_sgd: parameter views are written by the in-place form only");
     const int model_copy_dtype = mp ? mp->model_copy_dtype : XS_F16;
     if (model_copy && !is_half_dtype(model_copy_dtype))
         return fail(XS_ERR_UNSUPPORTED, "xs_fused_reduce_sgd: model_copy_dtype %d is not XS_F16 or XS_BF16",
@@ -441,7 +447,8 @@ int xs::reduce_sgd_impl(const Tuning &tn, const xs_plan *plan, const xs_tensor_h
                              out_of_place ? params_out : params,
                              out_of_place ? momentum_out : momentum, *hp, found_inf,
                              /*detect=*/out_of_place && found_inf != nullptr, model_copy,
-                             model_copy_dtype, tensor_hp ? plan : nullptr, tensor_hp, stream);
+                             model_copy_dtype, (tensor_hp || param_tensor_ptrs) ? plan : nullptr, tensor_hp,
+                             param_tensor_ptrs, view_dtype, stream);
 }
 
 extern "C" int xs_fused_reduce_sgd_mp(const void *const *replica_buckets, uint32_t W, int grad_dtype,
@@ -451,7 +458,7 @@ extern "C" int xs_fused_reduce_sgd_mp(const void *const *replica_buckets, uint32
                                       const xs_mp_options *mp, void *hip_stream)
 {
     return reduce_sgd_impl(tuning_now(), nullptr, nullptr, replica_buckets, W, grad_dtype, n_elems,
-                           params, momentum, params_out, momentum_out, hp, found_inf, mp,
+                           params, momentum, params_out, momentum_out, hp, found_inf, mp, nullptr,
                            (hipStream_t)hip_stream);
 }
 
@@ -471,7 +478,38 @@ int xs::reduce_sgd_pt_impl(const Tuning &tn, const xs_plan *gradient_plan,
     const xs_sgd_hparams hp = {0.f, 0.f, 0.f, inv_loss_scale};
     return reduce_sgd_impl(tn, gradient_plan, tensor_hp, replica_buckets, W, gradient_plan->dtype,
                            gradient_plan->bucket_elems, params, momentum, params_out,
-                           momentum_out, &hp, found_inf, mp, stream);
+                           momentum_out, &hp, found_inf, mp, nullptr, stream);
+}
+
+// "Receive averaged gradients" + "Model Update" + the way back to the per-layer tensors, one pass.
+int xs::reduce_sgd_unpack_impl(const Tuning &tn, const xs_plan *gradient_plan,
+                               const void *const *replica_buckets, uint32_t W, float *params,
+                               float *momentum, void *const *param_tensor_ptrs,
+                               const xs_sgd_hparams *hp, const xs_tensor_hparams *tensor_hp,
+                               int32_t *found_inf, const xs_mp_options *mp, hipStream_t stream)
+{
+    if (!gradient_plan || gradient_plan->magic != XS_PLAN_MAGIC)
+        return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd_unpack: plan is NULL or not a plan");
+    if (!hp) return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd_unpack: hp is NULL");
+    if (gradient_plan->bucket_elems == 0) return XS_OK;
+    if (!param_tensor_ptrs)
+        return fail(XS_ERR_INVALID_ARG, "xs_fused_reduce_sgd_unpack: param_tensor_ptrs is NULL");
+    if (tensor_hp && !aligned16(tensor_hp))
+        return fail(XS_ERR_ALIGNMENT, "xs_fused_reduce_sgd_unpack: tensor_hp is not 16-byte aligned");
+    return reduce_sgd_impl(tn, gradient_plan, tensor_hp, replica_buckets, W, gradient_plan->dtype,
+                           gradient_plan->bucket_elems, params, momentum, nullptr, nullptr, hp,
+                           found_inf, mp, param_tensor_ptrs, stream);
+}
+
+extern "C" int xs_fused_reduce_sgd_unpack(const xs_plan *gradient_plan, const void *const *replica_buckets,
+                                          uint32_t W, float *params, float *momentum,
+                                          void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
+                                          const xs_tensor_hparams *tensor_hp, int32_t *found_inf,
+                                          const xs_mp_options *mp, void *hip_stream)
+{
+    return reduce_sgd_unpack_impl(tuning_now(), gradient_plan, replica_buckets, W, params, momentum,
+                                  param_tensor_ptrs, hp, tensor_hp, found_inf, mp,
+                                  (hipStream_t)hip_stream);
 }
 
 extern "C" int xs_fused_reduce_sgd_pt(const xs_plan *gradient_plan, const void *const *replica_buckets,

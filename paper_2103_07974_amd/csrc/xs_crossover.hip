@@ -1,8 +1,9 @@
 // Two-stream crossover driver (arXiv 2103.07974, Algorithm 1 and Section 2.1).
 //
 // A task's gradient computation runs on the compute stream; its synchronisation
-// (the W packs in one launch, fused reduce + SGD, unpack; or the single gathering kernel when the task
-// was created with XS_APP_FUSED_GATHER) runs on the sync stream.  Two events per
+// (the W packs in one launch, fused reduce + SGD, unpack; the last two in one pass with
+// XS_APP_FUSED_UNPACK; or the single gathering kernel when the task was created with
+// XS_APP_FUSED_GATHER) runs on the sync stream.  Two events per
 // task carry the only dependencies the algorithm has:
 //   grads_ready  recorded on the compute stream after the task's computation;
 //                the task's synchronisation waits for it ("Send ... for gradient
@@ -63,8 +64,10 @@ extern "C" int xs_app_create(const xs_app_desc *d, xs_app **out)
     if (d->W == 0 || d->W > XS_MAX_REPLICAS)
         return fail(XS_ERR_INVALID_ARG, "xs_app_create: W = %u outside [1, %d]", d->W, XS_MAX_REPLICAS);
     const bool empty = d->gradient_plan->bucket_elems == 0;
-    if (d->flags & ~XS_APP_FUSED_GATHER)
+    if (d->flags & ~(XS_APP_FUSED_GATHER | XS_APP_FUSED_UNPACK))
         return fail(XS_ERR_UNSUPPORTED, "xs_app_create: unknown flags 0x%x", d->flags);
+    if ((d->flags & XS_APP_FUSED_GATHER) && (d->flags & XS_APP_FUSED_UNPACK))
+        return fail(XS_ERR_UNSUPPORTED, "xs_app_create: XS_APP_FUSED_GATHER and XS_APP_FUSED_UNPACK exclude each other");
     const bool gather = (d->flags & XS_APP_FUSED_GATHER) != 0;
     if (!empty && (!d->params || !d->momentum || !d->param_tensor_ptrs))
         return fail(XS_ERR_INVALID_ARG, "xs_app_create: a required pointer is NULL");
@@ -155,6 +158,10 @@ static int enqueue_sync(xs_app *a, hipStream_t s)
     int rc = fuse_pack_many_impl(tn, a->gplan, a->grad_tables.data(), a->buckets.data(), a->W,
                                  a->found_inf, s);
     if (rc != XS_OK) return rc;
+    if (a->flags & XS_APP_FUSED_UNPACK)
+        return reduce_sgd_unpack_impl(tn, a->gplan, (const void *const *)a->buckets.data(), a->W,
+                                      a->params, a->momentum, a->param_table, &a->hp, a->tensor_hp,
+                                      a->found_inf, nullptr, s);
     if (a->tensor_hp)
         rc = reduce_sgd_pt_impl(tn, a->gplan, (const void *const *)a->buckets.data(), a->W, a->params,
                                 a->momentum, nullptr, nullptr, a->tensor_hp, a->hp.inv_loss_scale,
@@ -162,7 +169,7 @@ static int enqueue_sync(xs_app *a, hipStream_t s)
     else
         rc = reduce_sgd_impl(tn, nullptr, nullptr, (const void *const *)a->buckets.data(), a->W,
                              a->gplan->dtype, a->gplan->bucket_elems, a->params, a->momentum, nullptr,
-                             nullptr, &a->hp, a->found_inf, nullptr, s);
+                             nullptr, &a->hp, a->found_inf, nullptr, nullptr, s);
     if (rc != XS_OK) return rc;
     return fuse_unpack_impl(tn, a->pplan, a->params, a->param_table, s);
 }

@@ -23,40 +23,6 @@
 
 namespace xs {
 
-template <int ALIGN>
-struct __attribute__((packed, aligned(ALIGN))) LooseVec16 {
-    u32x4 v;
-};
-struct __attribute__((packed, aligned(2))) LooseVec8 {
-    u32x2 v;
-};
-
-// element-aligned 16-byte load from a gradient tensor (non-temporal when it happens to be aligned)
-template <int ES>
-__device__ __forceinline__ u32x4 load_tensor_vec(const gbyte *p)
-{
-    if (((uintptr_t)p & 15u) == 0) return __builtin_nontemporal_load((const gvec *)p);
-    return ((const __attribute__((address_space(1))) LooseVec16<ES> *)p)->v;
-}
-
-// four updated parameters to a per-layer view: fp32 (16 bytes) or half precision (8 bytes)
-__device__ __forceinline__ void store_view4(gbyte *view, uint64_t elem, f32x4 x, int view_dtype)
-{
-    if (view_dtype == XS_F32) {
-        gbyte *p = view + elem * 4;
-        const u32x4 bits = __builtin_bit_cast(u32x4, x);
-        if (((uintptr_t)p & 15u) == 0) __builtin_nontemporal_store(bits, (gvec *)p);
-        else ((__attribute__((address_space(1))) LooseVec16<4> *)p)->v = bits;
-    } else {
-        ((__attribute__((address_space(1))) LooseVec8 *)(view + elem * 2))->v = to_half4(x, view_dtype);
-    }
-}
-__device__ __forceinline__ void store_view1(gbyte *view, uint64_t elem, float x, int view_dtype)
-{
-    if (view_dtype == XS_F32) *(__attribute__((address_space(1))) float *)(view + elem * 4) = x;
-    else *(__attribute__((address_space(1))) uint16_t *)(view + elem * 2) = to_half1(x, view_dtype);
-}
-
 struct GatherArgs {
     PlanTables tb;
     uint32_t n_tensors;

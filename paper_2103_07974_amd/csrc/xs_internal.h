@@ -101,9 +101,11 @@ int launch_reduce_sgd(const Tuning &tn, const void *const *replicas, uint32_t W,
                       const float *x_in, const float *v_in, float *x_out, float *v_out,
                       const xs_sgd_hparams &hp, int32_t *found_inf, bool detect,
                       void *model_copy, int model_copy_dtype, const xs_plan *plan,
-                      const xs_tensor_hparams *tensor_hp, hipStream_t stream);
-// plan + tensor_hp (both or neither): one (lr, momentum, weight decay) record per tensor of
-// the plan replaces hp's three; hp.inv_loss_scale always applies.
+                      const xs_tensor_hparams *tensor_hp, void *const *param_ptrs, int view_dtype,
+                      hipStream_t stream);
+// plan + tensor_hp: one (lr, momentum, weight decay) record per tensor of the plan replaces
+// hp's three; hp.inv_loss_scale always applies.  plan + param_ptrs: the updated parameters are
+// also written to the per-layer views (element type view_dtype) in the same pass.
 
 // The entry points' argument checks + launch under explicit launch settings (the extern "C"
 // functions pass tuning_now(); an xs_app passes its own settings if it has any).
@@ -116,7 +118,12 @@ int reduce_sgd_impl(const Tuning &tn, const xs_plan *plan, const xs_tensor_hpara
                     const void *const *replica_buckets, uint32_t W, int grad_dtype, uint64_t n_elems,
                     float *params, float *momentum, float *params_out, float *momentum_out,
                     const xs_sgd_hparams *hp, int32_t *found_inf, const xs_mp_options *mp,
-                    hipStream_t stream);
+                    void *const *param_tensor_ptrs, hipStream_t stream);
+int reduce_sgd_unpack_impl(const Tuning &tn, const xs_plan *gradient_plan,
+                           const void *const *replica_buckets, uint32_t W, float *params, float *momentum,
+                           void *const *param_tensor_ptrs, const xs_sgd_hparams *hp,
+                           const xs_tensor_hparams *tensor_hp, int32_t *found_inf,
+                           const xs_mp_options *mp, hipStream_t stream);
 int reduce_sgd_pt_impl(const Tuning &tn, const xs_plan *gradient_plan,
                        const void *const *replica_buckets, uint32_t W, float *params, float *momentum,
                        float *params_out, float *momentum_out, const xs_tensor_hparams *tensor_hp,

@@ -41,11 +41,14 @@ struct ReduceArgs {
     int32_t *found_inf;
     void *model_copy;       // half-precision copy of the updated parameters, or nullptr
     int model_copy_dtype;   // XS_F16 or XS_BF16
-    TensorHp thp;           // per-tensor records (kernels with PT = true only)
+    TensorHp thp;           // layout tables (PT or VIEWS) and per-tensor records (PT only)
+    const uint64_t *numel;        // device [n_tensors]                     (VIEWS only)
+    const uintptr_t *param_ptrs;  // device [n_tensors]: per-layer views    (VIEWS only)
+    int view_dtype;               // element type of the views
 };
 
 // One element of the ragged tail (fewer than VEC elements at the end of the bucket).
-template <int GT, bool DETECT, bool PT, typename Reps>
+template <int GT, bool DETECT, bool PT, bool VIEWS, typename Reps>
 __device__ __forceinline__ void tail_element(const Reps &reps, uint32_t W, const ReduceArgs &a,
                                              uint64_t j, bool &bad)
 {
@@ -70,6 +73,12 @@ __device__ __forceinline__ void tail_element(const Reps &reps, uint32_t W, const
     a.x_out[j] = xe;
     a.v_out[j] = ve;
     if (a.model_copy) ((uint16_t *)a.model_copy)[j] = to_half1(xe, a.model_copy_dtype);
+    if constexpr (VIEWS) {
+        uint32_t t = a.thp.row_first[j / ((uint64_t)kThreads * (16 / Grad<GT>::ES))];
+        seek_tensor(a.thp, t, j);
+        const uint64_t k = j - a.thp.offsets[t];
+        if (k < a.numel[t]) store_view1((gbyte *)a.param_ptrs[t], k, xe, a.view_dtype);
+    }
 }
 
 // The state vectors of one row of kThreads gradient vectors under per-tensor records: the
@@ -101,9 +110,59 @@ __device__ __forceinline__ RowHp row_hp(const TensorHp &h, uint64_t first_vec, u
     return r;
 }
 
+// The unpack fused into the pass (Section 2.1 read backwards: the per-layer tensors receive
+// the updated parameters): where a row's first element lives, and - when every element of
+// the row is a valid element of that one tensor, the rule - that tensor's offset and view
+// address through scalar loads.
+struct RowView {
+    uint32_t t_first;
+    bool uniform;
+    uint64_t off;
+    gbyte *view;
+};
+typedef const __attribute__((address_space(4))) uintptr_t cuptr;
+
+template <int VEC>
+__device__ __forceinline__ RowView row_view(const ReduceArgs &a, uint64_t first_vec)
+{
+    constexpr uint64_t ROW = (uint64_t)kThreads * VEC;
+    const uint32_t row = (uint32_t)__builtin_amdgcn_readfirstlane((int)(first_vec / kThreads));
+    RowView r;
+    r.t_first = (uint32_t)__builtin_amdgcn_readfirstlane((int)((cu32 *)a.thp.row_first)[row]);
+    const uint64_t row_end = ((uint64_t)row + 1) * ROW < a.n ? ((uint64_t)row + 1) * ROW : a.n;
+    r.off = ((cu64 *)a.thp.offsets)[r.t_first];
+    r.uniform = r.off + ((cu64 *)a.numel)[r.t_first] >= row_end;
+    r.view = (gbyte *)((cuptr *)a.param_ptrs)[r.t_first];
+    return r;
+}
+
+// four updated parameters that start at bucket element j go to their place in the views
+__device__ __forceinline__ void store_views4(const ReduceArgs &a, const RowView &rv, uint64_t j, f32x4 x)
+{
+    if (rv.uniform) {
+        store_view4(rv.view, j - rv.off, x, a.view_dtype);
+        return;
+    }
+    uint32_t t = rv.t_first;
+    seek_tensor(a.thp, t, j);
+    const uint64_t k = j - a.thp.offsets[t];
+    if (k + 4 <= a.numel[t]) {
+        store_view4((gbyte *)a.param_ptrs[t], k, x, a.view_dtype);
+        return;
+    }
+    // the vector touches padding or spans several tensors (tight layouts): element by element
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (j + q >= a.n) break;
+        seek_tensor(a.thp, t, j + q);
+        const uint64_t ke = j + q - a.thp.offsets[t];
+        if (ke < a.numel[t]) store_view1((gbyte *)a.param_ptrs[t], ke, x[q], a.view_dtype);
+    }
+}
+
 // VEC elements per lane per trip: 4 (fp32 gradients) or 8 (fp16 / bf16 gradients), so that
 // every gradient load is 16 bytes wide.
-template <int W, int GT, bool DETECT, bool NTG, bool NTS, bool PT>
+template <int W, int GT, bool DETECT, bool NTG, bool NTS, bool PT, bool VIEWS>
 __global__ __launch_bounds__(kMaxReduceThreads) void reduce_sgd_kernel(ReplicaPtrs<W> reps, ReduceArgs a)
 {
     constexpr bool HALF = Grad<GT>::HALF;
@@ -145,6 +204,8 @@ __global__ __launch_bounds__(kMaxReduceThreads) void reduce_sgd_kernel(ReplicaPt
         RowHp rh;
         if constexpr (PT) rh = row_hp<VEC>(a.thp, i - lane, a.n);
         else rh.rec = f32x4{a.lr, a.mu, a.wd, 0.f};
+        RowView rv;
+        if constexpr (VIEWS) rv = row_view<VEC>(a, i - lane);
         float s[VEC];
 #pragma unroll
         for (int w = 0; w < W; ++w) accumulate<GT, DETECT>(g[w], w == 0, s, bad);
@@ -160,13 +221,14 @@ __global__ __launch_bounds__(kMaxReduceThreads) void reduce_sgd_kernel(ReplicaPt
             store16f<NTS>((f32x4 *)a.v_out + sx[k], v[k]);
             if (a.model_copy)
                 store8<NTS>((u32x2 *)a.model_copy + sx[k], to_half4(x[k], a.model_copy_dtype));
+            if constexpr (VIEWS) store_views4(a, rv, sx[k] * 4, x[k]);
         }
     }
 
     // ragged tail: fewer than VEC elements, one lane each, in workgroup 0
     const uint32_t rem = (uint32_t)(a.n - nvec * VEC);
     if (blockIdx.x == 0 && threadIdx.x < rem)
-        tail_element<GT, DETECT, PT>(reps, (uint32_t)W, a, nvec * VEC + threadIdx.x, bad);
+        tail_element<GT, DETECT, PT, VIEWS>(reps, (uint32_t)W, a, nvec * VEC + threadIdx.x, bad);
 
     if constexpr (DETECT) {
         raise_flag_if(bad, a.found_inf);
@@ -175,7 +237,7 @@ __global__ __launch_bounds__(kMaxReduceThreads) void reduce_sgd_kernel(ReplicaPt
 
 // Any W up to XS_MAX_REPLICAS: replica loop with a run-time trip count, four loads in flight
 // at a time.  Same arithmetic and order as the specialised kernels; plain lane mapping.
-template <int GT, bool DETECT, bool PT>
+template <int GT, bool DETECT, bool PT, bool VIEWS>
 __global__ __launch_bounds__(kMaxReduceThreads) void reduce_sgd_anyw_kernel(
     ReplicaPtrs<XS_MAX_REPLICAS> reps, uint32_t W, ReduceArgs a)
 {
@@ -191,6 +253,8 @@ __global__ __launch_bounds__(kMaxReduceThreads) void reduce_sgd_anyw_kernel(
         RowHp rh;
         if constexpr (PT) rh = row_hp<VEC>(a.thp, i - lane, a.n);
         else rh.rec = f32x4{a.lr, a.mu, a.wd, 0.f};
+        RowView rv;
+        if constexpr (VIEWS) rv = row_view<VEC>(a, i - lane);
         float s[VEC];
         accumulate<GT, DETECT>(*((const u32x4 *)reps.p[0] + i), true, s, bad);
 #pragma unroll 4
@@ -205,11 +269,12 @@ __global__ __launch_bounds__(kMaxReduceThreads) void reduce_sgd_anyw_kernel(
             ((f32x4 *)a.x_out)[i * SV + k] = x;
             ((f32x4 *)a.v_out)[i * SV + k] = v;
             if (a.model_copy) ((u32x2 *)a.model_copy)[i * SV + k] = to_half4(x, a.model_copy_dtype);
+            if constexpr (VIEWS) store_views4(a, rv, (i * SV + k) * 4, x);
         }
     }
     const uint32_t rem = (uint32_t)(a.n - nvec * VEC);
     if (blockIdx.x == 0 && threadIdx.x < rem)
-        tail_element<GT, DETECT, PT>(reps, W, a, nvec * VEC + threadIdx.x, bad);
+        tail_element<GT, DETECT, PT, VIEWS>(reps, W, a, nvec * VEC + threadIdx.x, bad);
     if constexpr (DETECT) {
         raise_flag_if(bad, a.found_inf);
     }
@@ -224,20 +289,20 @@ struct Launch {
     hipStream_t stream;
 };
 
-template <int W, int GT, bool DETECT, bool NTG, bool NTS, bool PT>
+template <int W, int GT, bool DETECT, bool NTG, bool NTS, bool PT, bool VIEWS>
 static void launch_one(const Launch &l)
 {
     ReplicaPtrs<W> r;
     for (int w = 0; w < W; ++w) r.p[w] = l.replicas[w];
-    hipLaunchKernelGGL((reduce_sgd_kernel<W, GT, DETECT, NTG, NTS, PT>), l.grid, l.block,
+    hipLaunchKernelGGL((reduce_sgd_kernel<W, GT, DETECT, NTG, NTS, PT, VIEWS>), l.grid, l.block,
                        l.lds_reserve, l.stream, r, l.a);
 }
 
 template <int W, int GT, bool DETECT, bool NTG, bool NTS>
 static void launch_pt(const Launch &l)
 {
-    if (l.a.thp.rec != nullptr) launch_one<W, GT, DETECT, NTG, NTS, true>(l);
-    else launch_one<W, GT, DETECT, NTG, NTS, false>(l);
+    if (l.a.thp.rec != nullptr) launch_one<W, GT, DETECT, NTG, NTS, true, false>(l);
+    else launch_one<W, GT, DETECT, NTG, NTS, false, false>(l);
 }
 
 template <int W, int GT, bool DETECT>
@@ -250,6 +315,12 @@ static void launch_nt(const Launch &l, bool ntg, bool nts)
 template <int W, int GT>
 static void launch_gt(const Launch &l, bool detect, bool ntg, bool nts)
 {
+    if (l.a.param_ptrs != nullptr) {
+        // with the unpack fused in: in place, no in-kernel detection, every stream non-temporal
+        if (l.a.thp.rec != nullptr) launch_one<W, GT, false, true, true, true, true>(l);
+        else launch_one<W, GT, false, true, true, false, true>(l);
+        return;
+    }
     if (detect) launch_nt<W, GT, true>(l, ntg, nts);
     else launch_nt<W, GT, false>(l, ntg, nts);
 }
@@ -264,12 +335,12 @@ static void launch_w(const Launch &l, int dtype, bool detect, bool ntg, bool nts
     }
 }
 
-template <int GT, bool DETECT, bool PT>
+template <int GT, bool DETECT, bool PT, bool VIEWS>
 static void launch_anyw_one(const Launch &l, uint32_t W)
 {
     ReplicaPtrs<XS_MAX_REPLICAS> r;
     for (uint32_t w = 0; w < XS_MAX_REPLICAS; ++w) r.p[w] = w < W ? l.replicas[w] : nullptr;
-    hipLaunchKernelGGL((reduce_sgd_anyw_kernel<GT, DETECT, PT>), l.grid, l.block, l.lds_reserve,
+    hipLaunchKernelGGL((reduce_sgd_anyw_kernel<GT, DETECT, PT, VIEWS>), l.grid, l.block, l.lds_reserve,
                        l.stream, r, W, l.a);
 }
 
@@ -277,15 +348,20 @@ template <int GT>
 static void launch_anyw(const Launch &l, uint32_t W, bool detect)
 {
     const bool pt = l.a.thp.rec != nullptr;
-    if (detect) { if (pt) launch_anyw_one<GT, true, true>(l, W); else launch_anyw_one<GT, true, false>(l, W); }
-    else        { if (pt) launch_anyw_one<GT, false, true>(l, W); else launch_anyw_one<GT, false, false>(l, W); }
+    if (l.a.param_ptrs != nullptr) {
+        if (pt) launch_anyw_one<GT, false, true, true>(l, W); else launch_anyw_one<GT, false, false, true>(l, W);
+        return;
+    }
+    if (detect) { if (pt) launch_anyw_one<GT, true, true, false>(l, W); else launch_anyw_one<GT, true, false, false>(l, W); }
+    else        { if (pt) launch_anyw_one<GT, false, true, false>(l, W); else launch_anyw_one<GT, false, false, false>(l, W); }
 }
 
 int launch_reduce_sgd(const Tuning &tn, const void *const *replicas, uint32_t W, int dtype, uint64_t n,
                       const float *x_in, const float *v_in, float *x_out, float *v_out,
                       const xs_sgd_hparams &hp, int32_t *found_inf, bool detect,
                       void *model_copy, int model_copy_dtype, const xs_plan *plan,
-                      const xs_tensor_hparams *tensor_hp, hipStream_t stream)
+                      const xs_tensor_hparams *tensor_hp, void *const *param_ptrs, int view_dtype,
+                      hipStream_t stream)
 {
     const int cus = compute_units();
     if (cus < 0) return cus;
@@ -318,6 +394,10 @@ int launch_reduce_sgd(const Tuning &tn, const void *const *replicas, uint32_t W,
     l.a.thp.offsets = plan ? plan->tables.offsets : nullptr;
     l.a.thp.row_first = plan ? plan->tables.row_first : nullptr;
     l.a.thp.n_tensors = plan ? plan->n_tensors : 0;
+    // the unpack fused in needs the layout as well (plan) and is never combined with `detect`
+    l.a.numel = plan ? plan->tables.numel : nullptr;
+    l.a.param_ptrs = (plan && param_ptrs && !detect) ? (const uintptr_t *)param_ptrs : nullptr;
+    l.a.view_dtype = view_dtype;
     l.grid = dim3((unsigned)blocks);
     l.block = dim3((unsigned)threads);
     l.stream = stream;

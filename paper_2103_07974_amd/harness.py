@@ -53,13 +53,14 @@ class TaskState:
 
     def make_app(self, compute: Optional[Callable[[int], None]] = None,
                  use_found_inf: bool = False, fused_gather: bool = False,
-                 tensor_hp: Optional[torch.Tensor] = None, tuning=None) -> xs.App:
+                 tensor_hp: Optional[torch.Tensor] = None, tuning=None,
+                 fused_unpack: bool = False) -> xs.App:
         w = self.workload
         return xs.App(self.gplan, self.pplan, self.grad_tables, self.buckets, self.params,
                       self.momentum, self.param_table, w.lr, w.momentum, w.weight_decay,
                       1.0 / w.loss_scale, self.found_inf if use_found_inf else None, compute,
                       gather_table=self.gather_table if fused_gather else None, W=w.W,
-                      tensor_hp=tensor_hp, tuning=tuning)
+                      tensor_hp=tensor_hp, tuning=tuning, fused_unpack=fused_unpack)
 
 
 def make_task(w: wl.Workload, device="cuda", align: int = DEFAULT_ALIGN,

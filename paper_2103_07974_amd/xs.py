@@ -54,6 +54,7 @@ EXPORTS = [
     "xs_fuse_unpack",
     "xs_fused_reduce_sgd", "xs_fused_reduce_sgd_mp", "xs_fused_gather_reduce_sgd",
     "xs_fused_gather_reduce_sgd_mp", "xs_fused_reduce_sgd_pt", "xs_fused_gather_reduce_sgd_pt",
+    "xs_fused_reduce_sgd_unpack",
     "xs_app_create", "xs_app_destroy", "xs_app_sync", "xs_crossover_step",
     "xs_crossover_drain", "xs_crossover_iteration", "xs_crossover_finish", "xs_app_wait_sync",
     "xs_tuning_set", "xs_tuning_get", "xs_tuning_preset",
@@ -93,6 +94,7 @@ class AppDesc(ctypes.Structure):
 
 
 XS_APP_FUSED_GATHER = 1
+XS_APP_FUSED_UNPACK = 2
 
 
 _lib = None
@@ -136,6 +138,9 @@ def lib() -> ctypes.CDLL:
                                          ctypes.c_float, vp, ctypes.POINTER(MpOptions), vp]
     L.xs_fused_gather_reduce_sgd_pt.argtypes = [vp, vp, ctypes.c_uint32, vp, vp, vp, vp, vp, vp,
                                                 ctypes.c_float, vp, ctypes.POINTER(MpOptions), vp]
+    L.xs_fused_reduce_sgd_unpack.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_uint32, vp, vp, vp,
+                                             ctypes.POINTER(SgdHparams), vp, vp,
+                                             ctypes.POINTER(MpOptions), vp]
     L.xs_app_create.argtypes = [ctypes.POINTER(AppDesc), ctypes.POINTER(vp)]
     L.xs_app_destroy.argtypes = [vp]
     L.xs_app_sync.argtypes = [vp, vp]
@@ -373,6 +378,29 @@ def fused_reduce_sgd_pt(plan: Plan, replica_buckets: Sequence[torch.Tensor], par
                                         _stream_ptr(stream)), "xs_fused_reduce_sgd_pt")
 
 
+def fused_reduce_sgd_unpack(plan: Plan, replica_buckets: Sequence[torch.Tensor], params: torch.Tensor,
+                            momentum: torch.Tensor, param_tensor_ptrs: torch.Tensor, lr: float = 0.0,
+                            mu: float = 0.0, wd: float = 0.0, inv_loss_scale: float = 1.0,
+                            tensor_hp: Optional[torch.Tensor] = None,
+                            found_inf: Optional[torch.Tensor] = None, stream=None,
+                            view_dtype: torch.dtype = torch.float32,
+                            model_copy: Optional[torch.Tensor] = None) -> None:
+    """Bucket form, in place, with the unpack fused in: the per-layer views behind
+    param_tensor_ptrs (fp32, or fp16/bf16 with view_dtype) receive the updated parameters."""
+    W = len(replica_buckets)
+    arr = (ctypes.c_void_p * max(W, 1))(*[_dptr(b) for b in replica_buckets])
+    hp = SgdHparams(lr, mu, wd, inv_loss_scale)
+    mp = None
+    if view_dtype != torch.float32 or model_copy is not None:
+        mp = ctypes.byref(MpOptions(_dptr(model_copy),
+                                    dtype_code(model_copy.dtype) if model_copy is not None else XS_F16,
+                                    dtype_code(view_dtype)))
+    _check(lib().xs_fused_reduce_sgd_unpack(plan.handle, arr, W, _dptr(params), _dptr(momentum),
+                                            _dptr(param_tensor_ptrs), ctypes.byref(hp),
+                                            _dptr(tensor_hp), _dptr(found_inf), mp,
+                                            _stream_ptr(stream)), "xs_fused_reduce_sgd_unpack")
+
+
 def fused_gather_reduce_sgd_pt(plan: Plan, grad_ptrs: torch.Tensor, W: int, params: torch.Tensor,
                                momentum: torch.Tensor, tensor_hp: torch.Tensor,
                                inv_loss_scale: float = 1.0,
@@ -404,7 +432,7 @@ class App:
                  found_inf: Optional[torch.Tensor] = None, compute=None,
                  gather_table: Optional[torch.Tensor] = None, W: Optional[int] = None,
                  tensor_hp: Optional[torch.Tensor] = None,
-                 tuning: Optional[Sequence[int]] = None):
+                 tuning: Optional[Sequence[int]] = None, fused_unpack: bool = False):
         """With gather_table (device [tensor][worker] addresses) the app synchronises with the
         gathering kernel; grad_tables and replica_buckets may then be empty and W must be given.
         tensor_hp (device table from tensor_hparams_table) replaces lr/mu/wd per tensor.
@@ -434,7 +462,8 @@ class App:
         d.found_inf = _dptr(found_inf)
         d.compute = self._cb
         d.compute_ctx = None
-        d.flags = XS_APP_FUSED_GATHER if gather_table is not None else 0
+        d.flags = (XS_APP_FUSED_GATHER if gather_table is not None else 0) | \
+                  (XS_APP_FUSED_UNPACK if fused_unpack else 0)
         d.grad_ptrs_tw = _dptr(gather_table)
         d.tensor_hp = _dptr(tensor_hp)
         if tuning is not None:

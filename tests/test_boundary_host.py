@@ -153,6 +153,33 @@ def test_mixed_precision_option_validation():
     assert reduce_mp(FAKE + 0x5002, xs.XS_F16) == xs.XS_ERR_ALIGNMENT
     assert reduce_mp(FAKE + 0x1000, xs.XS_BF16) == xs.XS_ERR_INVALID_ARG     # on top of momentum
     assert reduce_mp(FAKE + 0x20010, xs.XS_F16) == xs.XS_ERR_INVALID_ARG     # on top of a replica
+    # the live half-precision model must not be written by a pass that may still be skipped:
+    # out-of-place outputs + found_inf (in-kernel detection) + model_copy is refused
+    mp = xs.MpOptions(FAKE + 0x5000, xs.XS_F16, 0)
+    rc = L.xs_fused_reduce_sgd_mp(arr, 2, xs.XS_F16, 16, FAKE, FAKE + 0x1000, FAKE + 0x2000, FAKE + 0x3000,
+                                  ctypes.byref(h), FAKE + 0x7000, ctypes.byref(mp), None)
+    assert rc == xs.XS_ERR_UNSUPPORTED and "model_copy" in xs.last_error()
+
+
+def test_launch_settings_presets_and_atomics():
+    L = xs.lib()
+    alone, beside = xs.tuning_preset(xs.PRESET_ALONE), xs.tuning_preset(xs.PRESET_BESIDE_COMPUTE)
+    assert len(alone) == xs.N_TUNING_KEYS and alone == [xs.tuning_get(k) for k in range(xs.N_TUNING_KEYS)]
+    assert beside[xs.TUNE_REDUCE_WAVES_PER_WG] == 4 and beside[xs.TUNE_REDUCE_LDS_RESERVE] == 82 * 1024
+    assert L.xs_tuning_preset(0, None) == xs.XS_ERR_INVALID_ARG
+    with pytest.raises(xs.XsError):
+        xs.tuning_preset(2)
+    for bad in (0, 3, 5):
+        with pytest.raises(xs.XsError):
+            xs.tuning_set(xs.TUNE_REDUCE_WAVES_PER_WG, bad)
+    # plan-less pack: layout errors and the size limit are found before anything touches a device
+    n = xs.STATIC_MAX_TENSORS + 1
+    numel = (ctypes.c_uint64 * n)(*([1] * n)); offs = (ctypes.c_uint64 * (n + 1))(*range(n + 1))
+    assert L.xs_fuse_pack_static(numel, offs, n, xs.XS_F32, FAKE, FAKE + 0x1000, None, None) == xs.XS_ERR_SIZE
+    assert "XS_STATIC_MAX_TENSORS" in xs.last_error()
+    assert L.xs_fuse_pack_static(numel, offs, 2, 7, FAKE, FAKE + 0x1000, None, None) == xs.XS_ERR_UNSUPPORTED
+    assert L.xs_fuse_pack_static(None, None, 2, xs.XS_F32, FAKE, FAKE + 0x1000, None, None) == xs.XS_ERR_INVALID_ARG
+    assert L.xs_fuse_pack_static(numel, offs, 0, xs.XS_F32, None, None, None, None) == xs.XS_OK
 
 
 def test_per_tensor_and_n_task_entry_points_reject_bad_handles():

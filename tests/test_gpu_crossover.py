@@ -216,3 +216,84 @@ def test_sync_overlaps_the_other_tasks_compute():
     torch.cuda.synchronize()
     assert done["compute_finished_when_sync_done"] is False
     a.destroy(); b.destroy()
+
+
+def test_overflow_inside_the_schedule_skips_one_step_and_resumes():
+    """Loss-scale overflow in the pack form: one computation of task b produces a non-finite
+    gradient; that synchronisation leaves b's state bit-identical, the caller clears the flag
+    on the sync stream behind every synchronisation of b (enqueue only), later iterations
+    resume, and task a is not affected.  The oracle skips the same step by its own rule."""
+    print("case crossover with one overflowed synchronisation", flush=True)
+    wls = [_mini("a", [(300, 7), (64,), (5000,)], W=2), _mini("b", [(17,), (9000, 3)], W=4)]
+    T, align, bad_call = 4, 8, 2
+    tasks = [harness.make_task(w, "cuda", align) for w in wls]
+    counters = [[0], [0]]
+
+    def compute_b(stream_ptr):
+        _device_compute(tasks[1], counters[1])(stream_ptr)
+        if counters[1][0] == bad_call:
+            s = torch.cuda.ExternalStream(stream_ptr)
+            with torch.cuda.stream(s):
+                tasks[1].grads[1][1].view(-1)[5:6].fill_(float("inf"))
+
+    apps = [tasks[0].make_app(_device_compute(tasks[0], counters[0]), use_found_inf=True),
+            tasks[1].make_app(compute_b, use_found_inf=True)]
+    cs, ss = torch.cuda.Stream(), torch.cuda.Stream()
+    seen = torch.zeros(2 * T + 2, dtype=torch.int32, device="cuda")
+    n_seen = 0
+
+    def after_sync(i):
+        nonlocal n_seen
+        if i == 1:       # look at b's flag behind its synchronisation, then clear it, on the sync stream
+            with torch.cuda.stream(ss):
+                seen[n_seen:n_seen + 1].copy_(tasks[1].found_inf)
+                tasks[1].found_inf.zero_()
+            n_seen += 1
+
+    prev = None
+    for t in range(T):
+        for i in range(2):
+            xs.crossover_step(apps[i], apps[prev] if prev is not None else None, cs, ss)
+            if prev is not None:
+                after_sync(prev)
+            prev = i
+    xs.crossover_drain(apps[prev], ss)
+    after_sync(prev)
+    torch.cuda.synchronize()
+    assert n_seen == T and seen[:n_seen].cpu().tolist() == [1 if k + 1 == bad_call else 0 for k in range(T)]
+    assert int(tasks[0].found_inf.item()) == 0
+
+    state = {"p": [[p.cpu().numpy().copy() for p in wl.make_params(w, "cuda")] for w in wls],
+             "v": [np.zeros(t.n_bucket, np.float32) for t in tasks], "count": [0, 0], "skipped": []}
+
+    def compute(i, t):
+        state["count"][i] += 1
+        g = _host_compute(state["p"][i], wls[i].W, state["count"][i])
+        if i == 1 and state["count"][i] == bad_call:
+            g[1][1].reshape(-1)[5] = np.inf
+        return g
+
+    def sync_update(i, g):
+        w = wls[i]
+        newp, found = oracle.sync_step(g, state["p"][i], state["v"][i], np.float32(w.lr).item(),
+                                       np.float32(w.momentum).item(), np.float32(w.weight_decay).item(),
+                                       1.0, align=align, precision="f32")
+        if found:
+            state["skipped"].append(i)
+        else:
+            state["p"][i] = newp
+    schedule.run_crossover(2, T, compute, sync_update)
+    assert state["skipped"] == [1]
+    for i, task in enumerate(tasks):
+        for got, want in zip(task.param_tensors, state["p"][i]):
+            assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
+        assert np.array_equal(task.momentum.cpu().numpy().view(np.uint32), state["v"][i].view(np.uint32))
+    for a in apps:
+        a.destroy()
+
+
+def test_gather_form_refuses_an_overflow_flag():
+    t = harness.make_task(_mini("g", [(100,), (7,)], W=2), "cuda", 4)
+    with pytest.raises(xs.XsError) as e:
+        t.make_app(fused_gather=True, use_found_inf=True)
+    assert e.value.status == xs.XS_ERR_UNSUPPORTED and "found_inf" in str(e.value)

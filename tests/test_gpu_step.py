@@ -126,6 +126,12 @@ def test_bert_large_f16_step_sampled_windows():
                                task.grads[r][t].view(torch.int16)), (t, r)
         assert torch.equal(task.param_tensors[t].view(torch.int32),
                            task.params[offs[t]:offs[t] + n].view(torch.int32))
+    # one worker's whole bucket (335 M half-precision elements) against the oracle's pack
+    r = 5
+    want = oracle.pack([t.cpu().numpy() for t in task.grads[r]], np.asarray(task.offsets, dtype=np.uint64))
+    got = task.buckets[r].cpu().numpy()
+    assert got.shape == want.shape and np.array_equal(_bits(got), _bits(want))
+    del want, got
     # properties that hold at any size: momentum changed everywhere gradients are non-zero
     assert not torch.equal(task.momentum, mom0)
     app.destroy()

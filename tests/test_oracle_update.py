@@ -190,6 +190,62 @@ def test_whole_step_equals_python_brute_force(prec, real, gdt):
     assert [float(e) for e in v] == [float(e) for e in bv]
 
 
+@pytest.mark.parametrize("W,gdt", [(8, np.float32), (16, np.float16), (3, np.float32), (13, np.float16)])
+def test_single_precision_order_of_operations_at_workload_width(W, gdt):
+    """The single-precision evaluation at the configured replica counts, against numpy float32
+    array arithmetic written out here (every numpy operation on float32 arrays rounds once):
+    left-to-right sum over workers, one constant c = inv_loss_scale * (1/W), then
+    d = g*c + wd*x, v = mu*v + d, x = x - lr*v.  Values follow the workloads' recipe.  The
+    same data summed pairwise, or scaled by inv_loss_scale / W, must differ somewhere, so the
+    pin is sensitive to both choices."""
+    rng = np.random.default_rng(100 + W)
+    n = 20000
+    scale = 1024.0 if gdt == np.float16 else 1.0
+    reps = [(rng.standard_normal(n) * 1e-3 * scale).astype(gdt) for _ in range(W)]
+    x0 = (rng.standard_normal(n) * 0.05).astype(np.float32)
+    v0 = (rng.standard_normal(n) * 0.01).astype(np.float32)
+    lr, mu, wd, inv = np.float32(0.1), np.float32(0.9), np.float32(1e-4), np.float32(1.0 / scale)
+
+    def by_hand(order="sequential", one_constant=True):
+        g = [r.astype(np.float32) for r in reps]
+        if order == "sequential":
+            s = g[0].copy()
+            for w in range(1, W):
+                s = s + g[w]
+        else:
+            level = g
+            while len(level) > 1:
+                level = [level[i] + level[i + 1] if i + 1 < len(level) else level[i]
+                         for i in range(0, len(level), 2)]
+            s = level[0]
+        if one_constant:
+            c = np.float32(inv * (np.float32(1.0) / np.float32(W)))
+            ga = s * c
+        else:
+            ga = (s * inv) / np.float32(W)
+        d = ga + wd * x0
+        v = mu * v0 + d
+        return (x0 - lr * v).astype(np.float32), v.astype(np.float32)
+
+    x, v = x0.copy(), v0.copy()
+    oracle.reduce_sgd_f32(reps, x, v, float(lr), float(mu), float(wd), float(inv))
+    hx, hv = by_hand()
+    assert np.array_equal(x.view(np.uint32), hx.view(np.uint32))
+    assert np.array_equal(v.view(np.uint32), hv.view(np.uint32))
+    # (three workers: the pairwise tree is the sequential sum; half-precision gradients: sums
+    # of 16 values of 11 significant bits are exact in single precision in any order)
+    if W >= 4 and gdt == np.float32:
+        px, pv = by_hand(order="pairwise")
+        assert not np.array_equal(v.view(np.uint32), pv.view(np.uint32))
+    if W in (3, 13):          # 1/W is not a power of two: one constant vs scale-then-divide differ
+        qx, qv = by_hand(one_constant=False)
+        assert not np.array_equal(v.view(np.uint32), qv.view(np.uint32))
+    # and the double-precision definition is within the single-precision error bound of it
+    x64, v64 = x0.astype(np.float64), v0.astype(np.float64)
+    oracle.reduce_sgd_f64(reps, x64, v64, float(lr), float(mu), float(wd), float(inv))
+    assert np.all(np.abs(x - x64) <= 1e-7 + 1e-6 * np.abs(x64))
+
+
 def test_aligned_layout_gives_same_tensors_as_tight():
     rng = np.random.default_rng(10)
     numel = [5, 64, 1, 130]
