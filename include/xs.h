@@ -317,9 +317,11 @@ typedef enum {
     XS_TUNE_GATHER_LDS_RESERVE = 8, /* as 4 for the gathering form; -1 = 8192 fp32, 16384 half */
     XS_TUNE_COPY_LDS_RESERVE = 9,   /* pack/unpack: bytes of LDS reserved per 256-lane workgroup beyond its
                                        tensor table; -1 (default) = 32768 */
-    XS_TUNE_REDUCE_WAVES_PER_WG = 10, /* reduce kernels: wavefronts per workgroup, 1 (default), 2 or 4.
-                                       The four wavefronts of a 4-wave workgroup land on the four SIMDs
-                                       of one compute unit */
+    XS_TUNE_REDUCE_WAVES_PER_WG = 10, /* gathering form and the generic-W bucket-form kernel (any W outside
+                                       2/4/8/16, or XS_TUNE_REDUCE_SMALL): wavefronts per workgroup, 1
+                                       (default), 2 or 4; the four wavefronts of a 4-wave workgroup land
+                                       on the four SIMDs of one compute unit.  The W-specialised
+                                       bucket-form kernels always use one-wavefront workgroups */
     XS_TUNE_REDUCE_SMALL = 11,      /* bucket-form reduce: 0 (default) = the kernel specialised for W with all
                                        W + 2 loads in flight (54 to 85 registers per lane); 1 = the
                                        generic-W kernel whatever W is: four replica loads in flight at a

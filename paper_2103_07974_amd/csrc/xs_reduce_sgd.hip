@@ -10,10 +10,12 @@
 //    every operation rounded to fp32 separately (-ffp-contract=off): bit-reproducible.
 //  * One-wavefront workgroups, one vector per lane, no loop in the default launch: workgroups
 //    are dispatched in address order as earlier ones retire, which keeps the DRAM access
-//    front tight (a strided persistent grid measured 25 % slower on MI355X).  A launch may
-//    ask for 2 or 4 wavefronts per workgroup instead (each wavefront still owns one row of
-//    64 vectors): a 4-wave workgroup puts one wavefront on every SIMD of its compute unit,
-//    which is how a synchronisation shares the compute units with another task's kernels.
+//    front tight (a strided persistent grid measured 25 % slower on MI355X).  The generic-W
+//    kernel (any W; also chosen by XS_TUNE_REDUCE_SMALL for its small register footprint)
+//    can be launched with 2 or 4 wavefronts per workgroup instead, each wavefront still
+//    owning one row of 64 vectors: a 4-wave workgroup puts one wavefront on every SIMD of
+//    its compute unit, which is how a synchronisation shares the compute units with another
+//    task's kernels.  The W-specialised kernels always run as one-wavefront workgroups.
 //  * The launch reserves LDS the kernel never touches, to cap how many wavefronts share a
 //    compute unit: about 100-120 KB of loads in flight per compute unit is the optimum.
 //  * Every stream is touched once, so loads and stores carry the non-temporal hint.
@@ -163,7 +165,7 @@ __device__ __forceinline__ void store_views4(const ReduceArgs &a, const RowView 
 // VEC elements per lane per trip: 4 (fp32 gradients) or 8 (fp16 / bf16 gradients), so that
 // every gradient load is 16 bytes wide.
 template <int W, int GT, bool DETECT, bool NTG, bool NTS, bool PT, bool VIEWS>
-__global__ __launch_bounds__(kMaxReduceThreads) void reduce_sgd_kernel(ReplicaPtrs<W> reps, ReduceArgs a)
+__global__ __launch_bounds__(kThreads) void reduce_sgd_kernel(ReplicaPtrs<W> reps, ReduceArgs a)
 {
     constexpr bool HALF = Grad<GT>::HALF;
     constexpr int VEC = 16 / Grad<GT>::ES;
@@ -171,11 +173,11 @@ __global__ __launch_bounds__(kMaxReduceThreads) void reduce_sgd_kernel(ReplicaPt
     if (a.found_inf != nullptr && *(volatile int32_t *)a.found_inf != 0) return;
 
     const uint64_t nvec = a.n / VEC;
-    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    const uint32_t lane = threadIdx.x & (kThreads - 1);
+    const uint64_t stride = (uint64_t)gridDim.x * kThreads;
+    const uint32_t lane = threadIdx.x;             // always launched with one-wavefront workgroups
     bool bad = false;
 
-    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
+    for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
         u32x4 g[W];
 #pragma unroll
         for (int w = 0; w < W; ++w) g[w] = load16<NTG>((const u32x4 *)reps.p[w] + i);
@@ -284,7 +286,8 @@ __global__ __launch_bounds__(kMaxReduceThreads) void reduce_sgd_anyw_kernel(
 struct Launch {
     const void *const *replicas;
     ReduceArgs a;
-    dim3 grid, block;
+    dim3 grid, block;   // the generic-W kernel: `block` lanes per workgroup
+    dim3 grid1;         // the W-specialised kernels: one wavefront per workgroup
     unsigned lds_reserve;
     hipStream_t stream;
 };
@@ -294,7 +297,7 @@ static void launch_one(const Launch &l)
 {
     ReplicaPtrs<W> r;
     for (int w = 0; w < W; ++w) r.p[w] = l.replicas[w];
-    hipLaunchKernelGGL((reduce_sgd_kernel<W, GT, DETECT, NTG, NTS, PT, VIEWS>), l.grid, l.block,
+    hipLaunchKernelGGL((reduce_sgd_kernel<W, GT, DETECT, NTG, NTS, PT, VIEWS>), l.grid1, dim3(kThreads),
                        l.lds_reserve, l.stream, r, l.a);
 }
 
@@ -368,15 +371,19 @@ int launch_reduce_sgd(const Tuning &tn, const void *const *replicas, uint32_t W,
     const bool half = dtype != XS_F32;
     const uint64_t vec = half ? 8 : 4;
     const uint64_t threads = (uint64_t)kThreads * (uint64_t)tn.reduce_waves_per_wg();
-    uint64_t blocks = (n / vec + threads - 1) / threads;
-    if (blocks == 0) blocks = 1;   // tail only
-    if (tn.reduce_wg_per_cu() > 0) {
-        const uint64_t cap = (uint64_t)cus * (uint64_t)tn.reduce_wg_per_cu();
-        if (blocks > cap) blocks = cap;
-    }
-    if (tn.reduce_max_wg() > 0 && blocks > (uint64_t)tn.reduce_max_wg())
-        blocks = (uint64_t)tn.reduce_max_wg();
-    if (blocks > 0x7fffffffull) blocks = 0x7fffffffull;   // the loop covers the rest
+    auto grid_for = [&](uint64_t lanes_per_wg) {
+        uint64_t blocks = (n / vec + lanes_per_wg - 1) / lanes_per_wg;
+        if (blocks == 0) blocks = 1;   // tail only
+        if (tn.reduce_wg_per_cu() > 0) {
+            const uint64_t cap = (uint64_t)cus * (uint64_t)tn.reduce_wg_per_cu();
+            if (blocks > cap) blocks = cap;
+        }
+        if (tn.reduce_max_wg() > 0 && blocks > (uint64_t)tn.reduce_max_wg())
+            blocks = (uint64_t)tn.reduce_max_wg();
+        if (blocks > 0x7fffffffull) blocks = 0x7fffffffull;   // the loop covers the rest
+        return blocks;
+    };
+    const uint64_t blocks = grid_for(threads), blocks1 = grid_for(kThreads);
 
     Launch l;
     l.replicas = replicas;
@@ -400,6 +407,7 @@ int launch_reduce_sgd(const Tuning &tn, const void *const *replicas, uint32_t W,
     l.a.view_dtype = view_dtype;
     l.grid = dim3((unsigned)blocks);
     l.block = dim3((unsigned)threads);
+    l.grid1 = dim3((unsigned)blocks1);
     l.stream = stream;
     // Measured on MI355X: the pass is fastest with 10 one-wave workgroups per compute unit
     // (fp32 W = 8: 12 loads per lane, about 120 KB in flight per compute unit; fp16 W = 16:

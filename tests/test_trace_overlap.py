@@ -33,6 +33,22 @@ def test_overlap_fraction_on_a_hand_made_trace(tmp_path):
     assert abs(r["stream_overlap_fraction"] - 0.7 / 0.9) < 1e-12
 
 
+def test_gemm_time_lost_beside_sync(tmp_path):
+    gemm = "Cijk_Ailk_Bljk_something"
+    sync = "void xs::copy_kernel<false>(...)"
+    rows = [(gemm, 0, 800_000), (gemm, 800_000, 1_600_000), (gemm, 1_600_000, 2_400_000),   # alone: 0.8 ms
+            (gemm, 2_400_000, 3_400_000), (gemm, 3_400_000, 4_500_000),                      # beside: 1.0, 1.1 ms
+            (sync, 2_500_000, 4_400_000),
+            (gemm, 4_500_000, 5_300_000)]
+    p = tmp_path / "t_kernel_trace.csv"
+    _write(p, rows)
+    r = trace_overlap.analyse(str(p))
+    assert r["gemm_kernels_alone"] == 4 and r["gemm_kernels_beside_sync"] == 2
+    assert abs(r["gemm_median_alone_us"] - 800.0) < 1e-9
+    assert abs(r["gemm_time_lost_beside_sync_ms"] - 0.5) < 1e-9
+    assert abs(r["sync_busy_time_ms"] - 1.9) < 1e-9
+
+
 def test_merge_and_classify():
     assert trace_overlap.merge([(5, 7), (0, 3), (2, 4), (7, 9)]) == [(0, 4), (5, 9)]
     assert trace_overlap.classify("void xs::copy_kernel<false>(...)") == "sync"

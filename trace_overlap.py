@@ -9,6 +9,9 @@ Kernels of libxs.so (namespace xs::) count as synchronisation; GEMM kernels (nam
 with Cijk_) and the arithmetic-only stand-in of bench_standin.hip count as compute.
 Only the part of the trace where both kinds appear within one millisecond of each other is
 used, so that stand-alone timing loops in the same trace do not dilute the figure.
+It also reports what the overlap costs the computation: the GEMM kernels that ran while a
+sync kernel was running against the median of those that ran alone (time lost), beside the
+time the sync stream was busy.
 """
 from __future__ import annotations
 
@@ -48,22 +51,37 @@ def overlap_with(iv: Tuple[int, int], merged: List[Tuple[int, int]]) -> int:
 
 
 def analyse(path: str, slack_ns: int = 1_000_000):
-    sync, comp = [], []
+    sync, comp, comp_named = [], [], []
     for r in csv.DictReader(open(path)):
         kind = classify(r["Kernel_Name"])
         if kind is None:
             continue
         iv = (int(r["Start_Timestamp"]), int(r["End_Timestamp"]))
         (sync if kind == "sync" else comp).append(iv)
+        if kind == "compute":
+            comp_named.append((iv, r["Kernel_Name"]))
     comp_m = merge(comp)
     # widen compute intervals by the slack to decide which sync kernels belong to the crossover phase
     near = merge([(a - slack_ns, b + slack_ns) for a, b in comp_m])
     used = [iv for iv in sync if overlap_with(iv, near) > 0]
     tot = sum(e - s for s, e in used)
     inside = sum(overlap_with(iv, comp_m) for iv in used)
+    # what the overlap costs the computation: GEMM kernels (one size per trace) that ran while
+    # a sync kernel was running, against the median duration of those that ran alone
+    sync_m = merge(used)
+    gemm = [iv for iv, nm in comp_named if nm.startswith("Cijk_")]
+    alone = sorted(e - s for s, e in gemm if overlap_with((s, e), sync_m) == 0)
+    beside = [e - s for s, e in gemm if overlap_with((s, e), sync_m) > 0]
+    base = alone[len(alone) // 2] if alone else None
+    stretch = sum(d - base for d in beside) if base is not None else None
     return {"sync_kernels_in_crossover_phase": len(used), "sync_kernels_total": len(sync),
             "sync_time_ms": tot / 1e6, "sync_time_inside_compute_ms": inside / 1e6,
-            "stream_overlap_fraction": inside / tot if tot else None}
+            "stream_overlap_fraction": inside / tot if tot else None,
+            "gemm_kernels_alone": len(alone), "gemm_median_alone_us": base / 1e3 if base else None,
+            "gemm_kernels_beside_sync": len(beside),
+            "gemm_median_beside_sync_us": sorted(beside)[len(beside) // 2] / 1e3 if beside else None,
+            "gemm_time_lost_beside_sync_ms": stretch / 1e6 if stretch is not None else None,
+            "sync_busy_time_ms": sum(e - s for s, e in sync_m) / 1e6}
 
 
 if __name__ == "__main__":
