@@ -18,7 +18,8 @@ Default run (what the one JSON line reports):
 Other modes (used for the summaries under profiles/):
   --kernels-only W      stand-alone launches of every kernel of workload W, nothing else
                         (rocprofv3 --kernel-trace --stats)
-  --traffic-probe       a calibration copy, then a few launches of every kernel (rocprofv3 --pmc)
+  --traffic-probe W     a calibration copy, then a few launches of every kernel of workload W
+                        (rocprofv3 --pmc)
   --stream-ceiling      plain 1:1 copy and 10-read : 2-write streaming kernels (attainable HBM rate)
   --crossover-sweep     the crossover pair under CU partitions and launch settings, one child
                         process per case (hipBLASLt reads its stream-K grid size once per process)
@@ -697,10 +698,13 @@ def kernels_only(name, launches):
     return 0
 
 
-def traffic_probe():
-    """A few launches for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: a plain device copy
-    of known size first (its counter reading calibrates the unit), then every kernel of the
-    path on the three large workloads."""
+def traffic_probe(name):
+    """A few launches for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`, one workload per
+    process: a plain device copy of known size first (its counter reading calibrates the
+    unit), then every kernel of the path.  Nothing is freed while the counters are collected
+    (the first version of this probe released its buffers between workloads inside one
+    profiled process and that process ended in a host-side segmentation fault inside the
+    profiling layer at the next allocation)."""
     import torch
     from paper_2103_07974_amd import harness, workloads as wl, xs
     xs.lib()
@@ -712,28 +716,27 @@ def traffic_probe():
     for _ in range(3):
         dst.copy_(src)
     torch.cuda.synchronize()
-    del src, dst
-    for w in (wl.RESNET50, wl.VGG16, wl.BERT_LARGE_F16):
-        task = harness.make_task(w, "cuda")
-        for _ in range(3):
-            xs.fuse_pack(task.gplan, task.grad_tables[0], task.buckets[0])
-            xs.fuse_pack_many(task.gplan, task.grad_tables, task.buckets)
-            xs.fused_reduce_sgd(task.buckets, task.n_bucket, task.params, task.momentum,
-                                w.lr, w.momentum, w.weight_decay, 1.0 / w.loss_scale)
-            xs.fuse_unpack(task.pplan, task.params, task.param_table)
-            xs.fused_reduce_sgd_unpack(task.gplan, task.buckets, task.params, task.momentum, task.param_table,
-                                       w.lr, w.momentum, w.weight_decay, 1.0 / w.loss_scale)
-            xs.fused_gather_reduce_sgd(task.gplan, task.gather_table, w.W, task.params,
-                                       task.momentum, w.lr, w.momentum, w.weight_decay, 1.0 / w.loss_scale,
-                                       param_tensor_ptrs=task.param_table)
-        torch.cuda.synchronize()
-        print(json.dumps({"workload": w.name, "copy_bytes_each_way": n * 4, "W": w.W,
-                          "reduce_bytes": task.reduce_bytes(), "pack_bytes_one_replica": task.pack_bytes(),
-                          "unpack_bytes": task.unpack_bytes(), "gather_bytes": task.gather_bytes(True),
-                          "reduce_fused_unpack_bytes": task.reduce_bytes() + 4 * w.n_elems,
-                          "bucket_elems": task.n_bucket}))
-        del task
-        torch.cuda.empty_cache()
+    w = wl.WORKLOADS[name]
+    # the largest set: all workers' tensor lists point at worker 0's tensors (the buckets stay
+    # distinct), which keeps the number of set-up launches under the counters small
+    task = harness.make_task(w, "cuda", shared_grads=name == "bert_large_f16")
+    for _ in range(3):
+        xs.fuse_pack(task.gplan, task.grad_tables[0], task.buckets[0])
+        xs.fuse_pack_many(task.gplan, task.grad_tables, task.buckets)
+        xs.fused_reduce_sgd(task.buckets, task.n_bucket, task.params, task.momentum,
+                            w.lr, w.momentum, w.weight_decay, 1.0 / w.loss_scale)
+        xs.fuse_unpack(task.pplan, task.params, task.param_table)
+        xs.fused_reduce_sgd_unpack(task.gplan, task.buckets, task.params, task.momentum, task.param_table,
+                                   w.lr, w.momentum, w.weight_decay, 1.0 / w.loss_scale)
+        xs.fused_gather_reduce_sgd(task.gplan, task.gather_table, w.W, task.params,
+                                   task.momentum, w.lr, w.momentum, w.weight_decay, 1.0 / w.loss_scale,
+                                   param_tensor_ptrs=task.param_table)
+    torch.cuda.synchronize()
+    print(json.dumps({"workload": w.name, "copy_bytes_each_way": n * 4, "W": w.W,
+                      "reduce_bytes": task.reduce_bytes(), "pack_bytes_one_replica": task.pack_bytes(),
+                      "unpack_bytes": task.unpack_bytes(), "gather_bytes": task.gather_bytes(True),
+                      "reduce_fused_unpack_bytes": task.reduce_bytes() + 4 * w.n_elems,
+                      "bucket_elems": task.n_bucket}))
     return 0
 
 
@@ -767,7 +770,7 @@ def main():
     ap.add_argument("--T", type=int, default=20, help="outer iterations of the crossover schedule")
     ap.add_argument("--kernels-only", metavar="WORKLOAD", help="resnet50 | vgg16 | bert_large_f16")
     ap.add_argument("--launches", type=int, default=60)
-    ap.add_argument("--traffic-probe", action="store_true")
+    ap.add_argument("--traffic-probe", metavar="WORKLOAD", help="resnet50 | vgg16 | bert_large_f16")
     ap.add_argument("--stream-ceiling", action="store_true")
     ap.add_argument("--power", action="store_true")
     ap.add_argument("--crossover-sweep", action="store_true")
@@ -792,7 +795,7 @@ def main():
     if args.kernels_only:
         return kernels_only(args.kernels_only, args.launches)
     if args.traffic_probe:
-        return traffic_probe()
+        return traffic_probe(args.traffic_probe)
     if args.stream_ceiling:
         return stream_ceiling()
     if args.power:

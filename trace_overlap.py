@@ -69,7 +69,11 @@ def analyse(path: str, slack_ns: int = 1_000_000):
     # what the overlap costs the computation: GEMM kernels (one size per trace) that ran while
     # a sync kernel was running, against the median duration of those that ran alone
     sync_m = merge(used)
-    gemm = [iv for iv, nm in comp_named if nm.startswith("Cijk_")]
+    # (only the GEMM kernel that shares the crossover phase: a trace may also hold the timing
+    # runs of other hipBLASLt algorithms)
+    names = [nm for iv, nm in comp_named if nm.startswith("Cijk_") and overlap_with(iv, sync_m) > 0]
+    main = max(set(names), key=names.count) if names else None
+    gemm = [iv for iv, nm in comp_named if nm == main]
     alone = sorted(e - s for s, e in gemm if overlap_with((s, e), sync_m) == 0)
     beside = [e - s for s, e in gemm if overlap_with((s, e), sync_m) > 0]
     base = alone[len(alone) // 2] if alone else None
