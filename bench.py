@@ -25,6 +25,7 @@ Other modes (used for the summaries under profiles/):
                         process per case (hipBLASLt reads its stream-K grid size once per process)
   --crossover-only      one short two-stream run and nothing else (rocprofv3 --kernel-trace)
   --power               board power and a clock proxy beside the GEMM chain / the sync kernels
+  --footprint           which register footprints are placed beside each GEMM algorithm's workgroups
 """
 from __future__ import annotations
 
@@ -45,7 +46,7 @@ METRIC = "fused grad-sync GB/s + % HBM roofline; crossover sync-hidden fraction 
 FROM_PROFILES = {
     "note": "copied from committed rocprofv3 summaries, not measured in this run",
     "reduce_sgd_vgg16_hbm_bytes_per_launch": {
-        "value": 6641210368, "algorithmic": 6641162112,
+        "value": 6641059267, "algorithmic": 6641162112,
         "file": "profiles/hbm_traffic_pmc_all_kernels.md"},
 }
 
@@ -225,16 +226,20 @@ class GemmChain:
         self.dim, self.chain = dim, chain
         self.label = f"{chain}x[{dim}x{dim}]@[{dim}x{dim}] bf16"
 
-    def fn(self, algo=0):
-        """Every chain starts from the same seeded Y (a 134 MB device copy in front of the 16
-        GEMMs): left to run on, Y @ B @ B ... overflows to inf/NaN after a few hundred products,
-        and a GEMM on such operands draws less power and runs 20 % faster on this chip."""
-        import bench_standin as bs
+    def enqueue(self, algo, stream_ptr, source=None, n=None):
+        """GEMM k reads the result of GEMM k-1; the first reads the seeded matrix, which is never
+        written.  (Left to run on from its own output, Y @ B @ B ... overflows to inf/NaN after a
+        few hundred products, and a GEMM on such operands draws less power and runs 20 % faster
+        on this chip.)"""
+        src = self.Y_init if source is None else source
+        for k in range(self.chain if n is None else n):
+            dst = self.Y[k & 1]
+            self.gemm.run(algo, src, self.B, dst, stream_ptr)
+            src = dst
 
+    def fn(self, algo=0):
         def compute(stream_ptr):
-            bs.copy(self.Y_init, self.Y[0], 16384, stream_ptr)
-            for k in range(self.chain):
-                self.gemm.run(algo, self.Y[k & 1], self.B, self.Y[1 - (k & 1)], stream_ptr)
+            self.enqueue(algo, stream_ptr)
         return compute
 
     def time_algo(self, algo, stream, reps=2):
@@ -260,10 +265,8 @@ class GemmChain:
         torch.cuda.synchronize()
         e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
         f1 = torch.cuda.Event(enable_timing=True)
-        bs.copy(self.Y_init, self.Y[0], 16384, cs)
         e0.record(cs)
-        for k in range(4):
-            self.gemm.run(algo, self.Y[k & 1], self.B, self.Y[1 - (k & 1)], cs)
+        self.enqueue(algo, cs, n=4)
         e1.record(cs)
         ss.wait_event(e0)
         bs.footprint(out, ts, 1024, 256, 82 * 1024, vgprs, 100, ss)
@@ -467,12 +470,14 @@ SWEEP = [
     ({"form": "packs", "k": 0, "algo": 0, "tuning": "beside"}, None),
     # two-sided partition: k compute units of every XCD for the sync stream, the rest for compute
     ({"form": "gather", "k": 1, "algo": 0}, None),
+    ({"form": "gather", "k": 1, "algo": 0}, 248),
     ({"form": "gather", "k": 1, "algo": 0}, 224),
     ({"form": "gather", "k": 2, "algo": 0}, 224),
     ({"form": "gather", "k": 4, "algo": 0}, 224),
     ({"form": "packs", "k": 4, "algo": 0}, 224),
     ({"form": "packs", "k": 8, "algo": 0}, 192),
     ({"form": "gather", "k": 8, "algo": 0}, 192),
+    ({"form": "gather", "k": 16, "algo": 0}, 128),
     # one-sided: only the sync stream is restricted
     ({"form": "gather", "k": 4, "algo": 0, "one_sided": True}, None),
 ]
@@ -556,6 +561,11 @@ def power_probe():
     def bg_gemm():
         gc.fn(0)(s1.cuda_stream)
 
+    nan_y = torch.full_like(gc.Y_init, float("nan"))
+
+    def bg_gemm_nan():          # the same GEMMs on operands that toggle no bits
+        gc.enqueue(0, s1.cuda_stream, source=nan_y)
+
     def bg_reduce():
         for _ in range(8):
             xs.fused_reduce_sgd(tb.buckets, tb.n_bucket, tb.params, tb.momentum, w.lr, w.momentum, w.weight_decay, 1.0, stream=s1)
@@ -574,23 +584,27 @@ def power_probe():
             app.sync(s3)
 
     def measure(name, background, with_alu, seconds=1.5):
-        alu_ms = []
+        alu_ms, bg_ms = [], []
         with Sampler() as p:
             t0 = time.time()
             while time.time() - t0 < seconds:
-                if background:
-                    background()
-                if with_alu:
+                t1 = time.perf_counter()
+                if with_alu:            # first, so that its 256 workgroups land one per compute unit
                     a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
                     a.record(s2); bs.alu(256, 400000, sink, s2); b.record(s2)
+                if background:
+                    background()
                 torch.cuda.synchronize()
+                bg_ms.append((time.perf_counter() - t1) * 1e3)
                 if with_alu:
                     alu_ms.append(a.elapsed_time(b))
         print(json.dumps({"busy_with": name, "power": p.stats(), "power_cap_W": cap_w,
+                          "ms_per_round_of_that_work": _median(bg_ms),
                           "fixed_arithmetic_kernel_ms": _median(alu_ms) if alu_ms else None}), flush=True)
 
     measure("idle (arithmetic kernel alone)", None, True)
-    measure("bf16 GEMM chain", bg_gemm, False)
+    measure("bf16 GEMM chain (16 GEMMs per round)", bg_gemm, False)
+    measure("the same GEMM chain on NaN operands", bg_gemm_nan, False)
     measure("fused reduce+SGD, vgg16", bg_reduce, False)
     measure("fused reduce+SGD, vgg16 + arithmetic kernel", bg_reduce, True)
     measure("8 packs per launch, vgg16", bg_packs, False)
@@ -598,6 +612,25 @@ def power_probe():
     measure("whole synchronisations, vgg16", bg_sync, False)
     measure("GEMM chain and whole synchronisations on two streams", bg_both, False)
     app.destroy()
+    return 0
+
+
+def footprint_probe():
+    """Which neighbours does a GEMM workgroup admit on its compute unit?  For the first
+    hipBLASLt algorithms: chain time alone, and the largest register footprint of a 4-wave
+    workgroup (82 KiB LDS reservation) that is still placed while the GEMMs run."""
+    import torch
+    import bench_standin as bs
+    bs.lib(); torch.cuda.set_device(0); torch.zeros(1, device="cuda")
+    gc = GemmChain()
+    cs, ss = torch.cuda.Stream(), torch.cuda.Stream()
+    for _ in range(3):
+        gc.time_algo(0, cs)
+    for algo in range(gc.gemm.n_algos):
+        ms = gc.time_algo(algo, cs)
+        fits = [v for v in (24, 48, 64, 72, 96, 128, 192, 256) if gc.admits_neighbours(algo, cs, ss, v)]
+        print(json.dumps({"gemm_algorithm_index": algo, "chain_ms": ms, "gemm_ms_each": ms / gc.chain,
+                          "largest_neighbour_registers_per_lane": max(fits) if fits else 0}), flush=True)
     return 0
 
 
@@ -773,6 +806,7 @@ def main():
     ap.add_argument("--traffic-probe", metavar="WORKLOAD", help="resnet50 | vgg16 | bert_large_f16")
     ap.add_argument("--stream-ceiling", action="store_true")
     ap.add_argument("--power", action="store_true")
+    ap.add_argument("--footprint", action="store_true")
     ap.add_argument("--crossover-sweep", action="store_true")
     ap.add_argument("--crossover-case", metavar="JSON")
     ap.add_argument("--crossover-only", action="store_true",
@@ -800,6 +834,8 @@ def main():
         return stream_ceiling()
     if args.power:
         return power_probe()
+    if args.footprint:
+        return footprint_probe()
 
     import torch
     import bench_standin as bs
@@ -930,6 +966,14 @@ def main():
             pair, [fs, fs], gc.label, T=args.T, form="packs", tuning=beside, streams=(cs, ss))
         alu, alu_label = alu_standin(x["packs_form"]["compute_alone_ms"][0])
         x["alu_standin_packs_form"] = crossover_run(pair, [alu, alu], alu_label, T=args.T, form="packs", streams=(cs, ss))
+        # the row-per-wavefront copy kernels fill every wave slot of the chip by default; a compute
+        # kernel of one long-lived workgroup per compute unit that is dispatched meanwhile lands
+        # unevenly and stays so.  A 16 KiB LDS reservation per copy workgroup (10 per compute unit)
+        # leaves it room, at a lower stand-alone copy rate.
+        capped = xs.tuning_preset(xs.PRESET_ALONE)
+        capped[xs.TUNE_COPY_LDS_RESERVE] = 16384
+        x["alu_standin_packs_form_copies_capped_10_per_cu"] = crossover_run(
+            pair, [alu, alu], alu_label, T=args.T, form="packs", tuning=capped, streams=(cs, ss))
         x["alu_standin_gather_form"] = crossover_run(pair, [alu, alu], alu_label, T=args.T, form="gather", streams=(cs, ss))
         # N = 3 tasks (Algorithm 1 is written for N): a second ResNet-50-shaped task joins
         third = harness.make_task(wl.RESNET50, "cuda")

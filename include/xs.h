@@ -304,8 +304,8 @@ typedef enum {
     XS_TUNE_REDUCE_WG_PER_CU = 0,   /* reduce kernels: workgroups per compute unit for a grid-stride
                                        launch; 0 (default) = one 16-byte vector per lane, no loop */
     XS_TUNE_COPY_WG_PER_CU = 1,     /* pack/unpack: workgroups per compute unit of a persistent grid;
-                                       0 (default) = one 16 KiB chunk per workgroup, dispatched in
-                                       bucket order (a few chunks when the tensor table is large) */
+                                       0 (default) = one KiB row of the bucket per wavefront, dispatched
+                                       in bucket order */
     XS_TUNE_NT_GRADS = 2,           /* bucket-form reduce: non-temporal gradient loads (0/1, default 1) */
     XS_TUNE_NT_STATE = 3,           /* bucket-form reduce: non-temporal parameter/momentum accesses (0/1, default 1) */
     XS_TUNE_REDUCE_LDS_RESERVE = 4, /* bytes of LDS reserved per reduce workgroup; the kernel uses no
@@ -315,8 +315,8 @@ typedef enum {
     XS_TUNE_COPY_MAX_WG = 6,        /* absolute cap on pack/unpack workgroups, 0 = none */
     XS_TUNE_COPY_NT = 7,            /* pack/unpack: non-temporal accesses (0/1, default 1) */
     XS_TUNE_GATHER_LDS_RESERVE = 8, /* as 4 for the gathering form; -1 = 8192 fp32, 16384 half */
-    XS_TUNE_COPY_LDS_RESERVE = 9,   /* pack/unpack: bytes of LDS reserved per 256-lane workgroup beyond its
-                                       tensor table; -1 (default) = 32768 */
+    XS_TUNE_COPY_LDS_RESERVE = 9,   /* pack/unpack: bytes of LDS reserved per workgroup (the kernel uses
+                                       none; caps the workgroups per compute unit); -1 (default) = 0 */
     XS_TUNE_REDUCE_WAVES_PER_WG = 10, /* gathering form and the generic-W bucket-form kernel (any W outside
                                        2/4/8/16, or XS_TUNE_REDUCE_SMALL): wavefronts per workgroup, 1
                                        (default), 2 or 4; the four wavefronts of a 4-wave workgroup land
@@ -326,7 +326,9 @@ typedef enum {
                                        W + 2 loads in flight (54 to 85 registers per lane); 1 = the
                                        generic-W kernel whatever W is: four replica loads in flight at a
                                        time, 28 (fp32) to 47 (fp16) registers per lane, same arithmetic */
-    XS_TUNE_COUNT = 12
+    XS_TUNE_COPY_WAVES_PER_WG = 12, /* pack/unpack: wavefronts per workgroup, 1 (default), 2 or 4; each
+                                       wavefront moves one KiB row of the bucket */
+    XS_TUNE_COUNT = 13
 } xs_tuning_key;
 int xs_tuning_set(int key, int value);
 int xs_tuning_get(int key, int *value_out);

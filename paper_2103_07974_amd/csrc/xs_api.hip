@@ -51,7 +51,8 @@ static const int kTuningDefault[XS_TUNE_COUNT] = {/*reduce_wg_per_cu*/ 0, /*copy
                                                  /*reduce_lds_reserve*/ -1, /*reduce_max_wg*/ 0,
                                                  /*copy_max_wg*/ 0, /*copy_nt*/ 1,
                                                  /*gather_lds_reserve*/ -1, /*copy_lds_reserve*/ -1,
-                                                 /*reduce_waves_per_wg*/ 1, /*reduce_small*/ 0};
+                                                 /*reduce_waves_per_wg*/ 1, /*reduce_small*/ 0,
+                                                 /*copy_waves_per_wg*/ 1};
 struct TuningRange {
     int lo, hi;
 };
@@ -68,16 +69,18 @@ static const TuningRange kTuningRange[XS_TUNE_COUNT] = {
     {-1, 131072},     // XS_TUNE_COPY_LDS_RESERVE
     {1, 4},           // XS_TUNE_REDUCE_WAVES_PER_WG (1, 2 or 4)
     {0, 1},           // XS_TUNE_REDUCE_SMALL
+    {1, 4},           // XS_TUNE_COPY_WAVES_PER_WG (1, 2 or 4)
 };
 static std::atomic<int> g_tuning[XS_TUNE_COUNT] = {
     {kTuningDefault[0]}, {kTuningDefault[1]}, {kTuningDefault[2]}, {kTuningDefault[3]},
     {kTuningDefault[4]}, {kTuningDefault[5]}, {kTuningDefault[6]}, {kTuningDefault[7]},
-    {kTuningDefault[8]}, {kTuningDefault[9]}, {kTuningDefault[10]}, {kTuningDefault[11]}};
+    {kTuningDefault[8]}, {kTuningDefault[9]}, {kTuningDefault[10]}, {kTuningDefault[11]},
+    {kTuningDefault[12]}};
 
 static bool tuning_value_ok(int key, int value)
 {
     if (value < kTuningRange[key].lo || value > kTuningRange[key].hi) return false;
-    return key != XS_TUNE_REDUCE_WAVES_PER_WG || value != 3;
+    return (key != XS_TUNE_REDUCE_WAVES_PER_WG && key != XS_TUNE_COPY_WAVES_PER_WG) || value != 3;
 }
 
 Tuning tuning_now()
@@ -154,7 +157,7 @@ extern "C" int xs_tuning_preset(int preset, int32_t *values_out)
         values_out[XS_TUNE_GATHER_LDS_RESERVE] = 82 * 1024;
         values_out[XS_TUNE_COPY_LDS_RESERVE] = 82 * 1024;
         values_out[XS_TUNE_REDUCE_SMALL] = 1;   // 28-47 registers per lane
-        values_out[XS_TUNE_COPY_NT] = 0;        // unpack: 46 registers instead of 50
+        values_out[XS_TUNE_COPY_WAVES_PER_WG] = 4;
         return XS_OK;
     default: return fail(XS_ERR_INVALID_ARG, "xs_tuning_preset: unknown preset %d", preset);
     }

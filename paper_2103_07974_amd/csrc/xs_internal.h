@@ -42,6 +42,7 @@ struct Tuning {
     int copy_lds_reserve() const { return v[XS_TUNE_COPY_LDS_RESERVE]; }
     int reduce_waves_per_wg() const { return v[XS_TUNE_REDUCE_WAVES_PER_WG]; }
     bool reduce_small() const { return v[XS_TUNE_REDUCE_SMALL] != 0; }
+    int copy_waves_per_wg() const { return v[XS_TUNE_COPY_WAVES_PER_WG]; }
 };
 Tuning tuning_now();                                   // snapshot of the process-wide settings
 int tuning_check(const int32_t *values, Tuning *out);  // XS_OK, or which value is out of range

@@ -43,7 +43,8 @@ TUNE_GATHER_LDS_RESERVE = 8
 TUNE_COPY_LDS_RESERVE = 9
 TUNE_REDUCE_WAVES_PER_WG = 10
 TUNE_REDUCE_SMALL = 11
-N_TUNING_KEYS = 12
+TUNE_COPY_WAVES_PER_WG = 12
+N_TUNING_KEYS = 13
 
 PRESET_ALONE = 0
 PRESET_BESIDE_COMPUTE = 1

@@ -28,10 +28,12 @@ def _settings(**kw):
 
 VARIANTS = {
     "beside": lambda: xs.tuning_preset(xs.PRESET_BESIDE_COMPUTE),
-    "2 waves": lambda: _settings(REDUCE_WAVES_PER_WG=2),
-    "4 waves, persistent": lambda: _settings(REDUCE_WAVES_PER_WG=4, REDUCE_WG_PER_CU=2, COPY_WG_PER_CU=3),
+    "2 waves": lambda: _settings(REDUCE_WAVES_PER_WG=2, COPY_WAVES_PER_WG=2),
+    "4 waves, persistent": lambda: _settings(REDUCE_WAVES_PER_WG=4, REDUCE_WG_PER_CU=2, COPY_WG_PER_CU=3,
+                                             COPY_WAVES_PER_WG=4, COPY_LDS_RESERVE=40960, COPY_NT=0),
     "small kernel": lambda: _settings(REDUCE_SMALL=1),
-    "4 waves, 7 workgroups": lambda: _settings(REDUCE_WAVES_PER_WG=4, REDUCE_MAX_WG=7, COPY_MAX_WG=5),
+    "4 waves, 7 workgroups": lambda: _settings(REDUCE_WAVES_PER_WG=4, REDUCE_MAX_WG=7, COPY_MAX_WG=5,
+                                               COPY_WAVES_PER_WG=2),
 }
 
 
@@ -69,5 +71,5 @@ def test_invalid_settings_are_refused():
     with pytest.raises(xs.XsError):
         xs.tuning_preset(7)
     pre = xs.tuning_preset(xs.PRESET_BESIDE_COMPUTE)
-    assert pre[xs.TUNE_REDUCE_WAVES_PER_WG] == 4 and pre[xs.TUNE_REDUCE_SMALL] == 1
+    assert pre[xs.TUNE_REDUCE_WAVES_PER_WG] == 4 and pre[xs.TUNE_REDUCE_SMALL] == 1 and pre[xs.TUNE_COPY_WAVES_PER_WG] == 4
     assert xs.tuning_preset(xs.PRESET_ALONE) == [xs.tuning_get(k) for k in range(xs.N_TUNING_KEYS)]
