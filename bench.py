@@ -817,6 +817,9 @@ def main():
                     help="how much slower than the fastest GEMM algorithm the sharing one may be")
     ap.add_argument("--beside", action="store_true", help="XS_PRESET_BESIDE_COMPUTE for the synchronisations")
     ap.add_argument("--autograd", action="store_true", help="with --crossover-only: the two autograd MLP tasks")
+    ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
+                    help="with --crossover-only: one launch setting of the synchronisations, by the name of its "
+                         "key without the XS_TUNE_ prefix (e.g. REDUCE_WG_PER_CU=2); may be repeated")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the W workers' gradients are resident "
@@ -847,6 +850,11 @@ def main():
     if args.crossover_only:
         cs, ss = torch.cuda.Stream(), torch.cuda.Stream()
         tuning = xs.tuning_preset(xs.PRESET_BESIDE_COMPUTE) if args.beside else None
+        if args.tune:
+            tuning = tuning if tuning is not None else xs.tuning_preset(xs.PRESET_ALONE)
+            for item in args.tune:
+                name, _, value = item.partition("=")
+                tuning[getattr(xs, "TUNE_" + name)] = int(value)
         if args.autograd:
             ma = harness.make_mlp_task("mlp_6x4096", [4096] * 7, W=4, batch=256, seed=31)
             mb = harness.make_mlp_task("mlp_8192_wide", [2048, 8192, 8192, 2048], W=4, batch=256, seed=32)
