@@ -792,6 +792,53 @@ def stream_ceiling():
     return 0
 
 
+def few_cu_sweep():
+    """The VGG-16-shaped synchronisation alone on a stream that owns k compute units of every
+    XCD, for several launch shapes: what a synchronisation confined to few compute units can
+    move, per compute unit and in all."""
+    import torch
+    import bench_standin as bs
+    from paper_2103_07974_amd import harness, workloads as wl, xs
+    xs.lib(); bs.lib(); torch.cuda.set_device(0); torch.zeros(1, device="cuda")
+    w = wl.VGG16
+    tb = harness.make_task(w, "cuda")
+
+    def tuned(**kw):
+        t = xs.tuning_preset(xs.PRESET_ALONE)
+        for name, v in kw.items():
+            t[getattr(xs, "TUNE_" + name)] = v
+        return t
+    shapes = [
+        ("default: one row per one-wave workgroup, 20 resident per CU", tuned()),
+        ("10 resident per CU", tuned(GATHER_LDS_RESERVE=16384)),
+        ("as many as the registers allow", tuned(GATHER_LDS_RESERVE=0)),
+        ("persistent grid, 10 one-wave workgroups per CU of the chip", tuned(REDUCE_WG_PER_CU=10, GATHER_LDS_RESERVE=0)),
+        ("4-wave workgroups, 5 resident per CU", tuned(REDUCE_WAVES_PER_WG=4, GATHER_LDS_RESERVE=32768)),
+    ]
+    nbytes = tb.gather_bytes()
+    for k in (1, 2, 4, 8, 32):
+        if k == 32:
+            stream, n_cus, ms = torch.cuda.Stream(), 256, None
+        else:
+            ms = bs.MaskedStream(bs.sync_and_compute_masks(k)[0])
+            stream, n_cus = ms.stream, len(bs.census(4096, 2000, ms.stream))
+        for label, tn in shapes:
+            app = tb.make_app(None, tuning=tn, fused_gather=True)
+            for _ in range(2):
+                app.sync(stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            n = 3 if k < 4 else 10
+            for _ in range(n):
+                app.sync(stream)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) * 1e3 / n
+            app.destroy()
+            print(json.dumps({"compute_units": n_cus, "launch": label, "sync_ms": dt, "GBs": nbytes / dt / 1e6,
+                              "GBs_per_compute_unit": nbytes / dt / 1e6 / n_cus}), flush=True)
+    return 0
+
+
 # --------------------------------------------------------------------------- main
 def main():
     ap = argparse.ArgumentParser()
@@ -807,6 +854,7 @@ def main():
     ap.add_argument("--stream-ceiling", action="store_true")
     ap.add_argument("--power", action="store_true")
     ap.add_argument("--footprint", action="store_true")
+    ap.add_argument("--few-cu-sweep", action="store_true")
     ap.add_argument("--crossover-sweep", action="store_true")
     ap.add_argument("--crossover-case", metavar="JSON")
     ap.add_argument("--crossover-only", action="store_true",
@@ -839,6 +887,8 @@ def main():
         return power_probe()
     if args.footprint:
         return footprint_probe()
+    if args.few_cu_sweep:
+        return few_cu_sweep()
 
     import torch
     import bench_standin as bs
