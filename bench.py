@@ -1019,19 +1019,19 @@ def main():
         x["packs_form"] = crossover_run(pair, [f0, f0], gc.label, T=args.T, form="packs", streams=(cs, ss))
         x["gather_form"] = crossover_run(pair, [f0, f0], gc.label, T=args.T, form="gather", streams=(cs, ss))
         x["fused_unpack_form"] = crossover_run(pair, [f0, f0], gc.label, T=args.T, form="fused_unpack", streams=(cs, ss))
-        x["packs_form_sharing_gemm_kernel"] = crossover_run(pair, [fs, fs], gc.label, T=args.T, form="packs", streams=(cs, ss))
+        ref = x["packs_form"]["t_comp_ms"]
+        x["packs_form_sharing_gemm_kernel"] = crossover_run(pair, [fs, fs], gc.label, T=args.T, form="packs", streams=(cs, ss),
+                                                            t_comp_reference=ref)
         x["packs_form_sharing_gemm_kernel_beside_preset"] = crossover_run(
-            pair, [fs, fs], gc.label, T=args.T, form="packs", tuning=beside, streams=(cs, ss))
+            pair, [fs, fs], gc.label, T=args.T, form="packs", tuning=beside, streams=(cs, ss), t_comp_reference=ref)
         alu, alu_label = alu_standin(x["packs_form"]["compute_alone_ms"][0])
         x["alu_standin_packs_form"] = crossover_run(pair, [alu, alu], alu_label, T=args.T, form="packs", streams=(cs, ss))
         # the row-per-wavefront copy kernels fill every wave slot of the chip by default; a compute
         # kernel of one long-lived workgroup per compute unit that is dispatched meanwhile lands
-        # unevenly and stays so.  A 16 KiB LDS reservation per copy workgroup (10 per compute unit)
-        # leaves it room, at a lower stand-alone copy rate.
-        capped = xs.tuning_preset(xs.PRESET_ALONE)
-        capped[xs.TUNE_COPY_LDS_RESERVE] = 16384
-        x["alu_standin_packs_form_copies_capped_10_per_cu"] = crossover_run(
-            pair, [alu, alu], alu_label, T=args.T, form="packs", tuning=capped, streams=(cs, ss))
+        # unevenly and stays so.  XS_PRESET_LEAVE_WAVE_SLOTS caps the copies at 10 per compute unit.
+        x["alu_standin_packs_form_leave_wave_slots_preset"] = crossover_run(
+            pair, [alu, alu], alu_label, T=args.T, form="packs",
+            tuning=xs.tuning_preset(xs.PRESET_LEAVE_WAVE_SLOTS), streams=(cs, ss))
         x["alu_standin_gather_form"] = crossover_run(pair, [alu, alu], alu_label, T=args.T, form="gather", streams=(cs, ss))
         # N = 3 tasks (Algorithm 1 is written for N): a second ResNet-50-shaped task joins
         third = harness.make_task(wl.RESNET50, "cuda")
@@ -1040,8 +1040,13 @@ def main():
         x["n3_alu_standin_gather_form"] = crossover_run([resnet, vgg, third], [alu, alu, alu], alu_label,
                                                         T=max(4, args.T // 2), form="gather", streams=(cs, ss))
         del third
+        # every case against the computation with the library's own GEMM kernel (a slower GEMM
+        # that shares its compute units must make up for its own slowness first)
+        def strict(k):
+            v = x[k].get("hidden_fraction_vs_unrestricted_compute")
+            return x[k]["end_to_end_hidden_fraction"] if v is None else v
         best_key = max((k for k in x if "alu" not in k and "n3" not in k and x[k].get("end_to_end_hidden_fraction") is not None),
-                       key=lambda k: x[k]["end_to_end_hidden_fraction"])
+                       key=strict)
         x["gemm_chain_ms_by_algorithm"] = {str(a): t for a, t in algo_ms.items()}
         x["gemm_algorithm_that_admits_neighbours"] = share_algo
         extra["crossover"] = x
@@ -1068,10 +1073,11 @@ def main():
             "target": 0.90,
             "target_met": bool(c["end_to_end_hidden_fraction"] is not None and c["end_to_end_hidden_fraction"] >= 0.90),
             "speedup_vs_serial": c["speedup_vs_serial"],
-            "best_of_the_library_s_forms_and_settings": {"which": best_key,
-                                                         "end_to_end_hidden_fraction": x[best_key]["end_to_end_hidden_fraction"]},
-            "why": "the bf16 GEMM chain and the HBM-bound synchronisation kernels each run at the board's 1400 W "
-                   "power limit, so overlapping them cannot shorten the schedule "
+            "best_of_the_library_s_forms_and_settings": {"which": best_key, "end_to_end_hidden_fraction": strict(best_key)},
+            "why": "the bf16 GEMM chain alone runs at the board's 1400 W power limit and its kernel owns every "
+                   "compute unit whole; the HBM-bound synchronisation kernels draw 1.0-1.2 kW themselves, so what "
+                   "runs beside the GEMMs is paid back in GEMM time, and every partition of the compute units costs "
+                   "the GEMM more than the synchronisations take "
                    "(profiles/crossover_config4_partition_sweep_and_power.md)",
             "other_figures_that_are_not_the_target_metric": {
                 "iterations_whose_sync_outlasted_the_compute_beside_it": c["iterations_whose_sync_outlasted_the_compute_beside_it"],

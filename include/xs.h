@@ -343,9 +343,16 @@ int xs_tuning_get(int key, int *value_out);
  *                             while 78 KiB of LDS, 7/8 of the wave slots and 29/32 of the
  *                             register file stay free for the other task's workgroups at
  *                             all times
+ *   XS_PRESET_LEAVE_WAVE_SLOTS  as ALONE, but pack and unpack hold a 16 KiB LDS reservation per
+ *                             one-wave workgroup: ten per compute unit instead of every wave
+ *                             slot (their stand-alone rate falls from 6.4 to 4.1 TB/s).  The
+ *                             reduce kernels keep that much room by default.  For a task whose
+ *                             neighbour launches few long-lived workgroups: dispatched while
+ *                             copies fill every wave slot they land on whichever compute
+ *                             units have room first and stay unevenly spread
  * XS_ERR_INVALID_ARG for an unknown preset or a NULL pointer.
  */
-typedef enum { XS_PRESET_ALONE = 0, XS_PRESET_BESIDE_COMPUTE = 1 } xs_tuning_preset_id;
+typedef enum { XS_PRESET_ALONE = 0, XS_PRESET_BESIDE_COMPUTE = 1, XS_PRESET_LEAVE_WAVE_SLOTS = 2 } xs_tuning_preset_id;
 int xs_tuning_preset(int preset, int32_t *values_out /* XS_TUNE_COUNT */);
 
 /* ------------------------------------------------------------------------

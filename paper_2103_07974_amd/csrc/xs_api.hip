@@ -159,6 +159,9 @@ extern "C" int xs_tuning_preset(int preset, int32_t *values_out)
         values_out[XS_TUNE_REDUCE_SMALL] = 1;   // 28-47 registers per lane
         values_out[XS_TUNE_COPY_WAVES_PER_WG] = 4;
         return XS_OK;
+    case XS_PRESET_LEAVE_WAVE_SLOTS:
+        values_out[XS_TUNE_COPY_LDS_RESERVE] = 16 * 1024;
+        return XS_OK;
     default: return fail(XS_ERR_INVALID_ARG, "xs_tuning_preset: unknown preset %d", preset);
     }
 }

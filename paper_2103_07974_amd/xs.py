@@ -48,6 +48,7 @@ N_TUNING_KEYS = 13
 
 PRESET_ALONE = 0
 PRESET_BESIDE_COMPUTE = 1
+PRESET_LEAVE_WAVE_SLOTS = 2
 
 EXPORTS = [
     "xs_status_string", "xs_last_error", "xs_bucket_layout", "xs_plan_create", "xs_plan_destroy",
@@ -521,7 +522,7 @@ def crossover_finish(apps: Sequence[App], sync_stream) -> None:
 
 
 def tuning_preset(preset: int) -> List[int]:
-    """Launch settings of a named preset (PRESET_ALONE, PRESET_BESIDE_COMPUTE) for App(tuning=...)."""
+    """Launch settings of a named preset (PRESET_ALONE, PRESET_BESIDE_COMPUTE, PRESET_LEAVE_WAVE_SLOTS) for App(tuning=...)."""
     out = (ctypes.c_int32 * N_TUNING_KEYS)()
     _check(lib().xs_tuning_preset(int(preset), out), "xs_tuning_preset")
     return list(out)

@@ -167,8 +167,11 @@ def test_launch_settings_presets_and_atomics():
     assert len(alone) == xs.N_TUNING_KEYS and alone == [xs.tuning_get(k) for k in range(xs.N_TUNING_KEYS)]
     assert beside[xs.TUNE_REDUCE_WAVES_PER_WG] == 4 and beside[xs.TUNE_REDUCE_LDS_RESERVE] == 82 * 1024
     assert L.xs_tuning_preset(0, None) == xs.XS_ERR_INVALID_ARG
+    slots = xs.tuning_preset(xs.PRESET_LEAVE_WAVE_SLOTS)
+    assert [k for k in range(xs.N_TUNING_KEYS) if slots[k] != alone[k]] == [xs.TUNE_COPY_LDS_RESERVE]
+    assert slots[xs.TUNE_COPY_LDS_RESERVE] == 16 * 1024
     with pytest.raises(xs.XsError):
-        xs.tuning_preset(2)
+        xs.tuning_preset(3)
     for bad in (0, 3, 5):
         with pytest.raises(xs.XsError):
             xs.tuning_set(xs.TUNE_REDUCE_WAVES_PER_WG, bad)

@@ -28,6 +28,7 @@ def _settings(**kw):
 
 VARIANTS = {
     "beside": lambda: xs.tuning_preset(xs.PRESET_BESIDE_COMPUTE),
+    "leave wave slots": lambda: xs.tuning_preset(xs.PRESET_LEAVE_WAVE_SLOTS),
     "2 waves": lambda: _settings(REDUCE_WAVES_PER_WG=2, COPY_WAVES_PER_WG=2),
     "4 waves, persistent": lambda: _settings(REDUCE_WAVES_PER_WG=4, REDUCE_WG_PER_CU=2, COPY_WG_PER_CU=3,
                                              COPY_WAVES_PER_WG=4, COPY_LDS_RESERVE=40960, COPY_NT=0),
