@@ -1019,26 +1019,27 @@ def main():
         x["packs_form"] = crossover_run(pair, [f0, f0], gc.label, T=args.T, form="packs", streams=(cs, ss))
         x["gather_form"] = crossover_run(pair, [f0, f0], gc.label, T=args.T, form="gather", streams=(cs, ss))
         x["fused_unpack_form"] = crossover_run(pair, [f0, f0], gc.label, T=args.T, form="fused_unpack", streams=(cs, ss))
-        ref = x["packs_form"]["t_comp_ms"]
-        x["packs_form_sharing_gemm_kernel"] = crossover_run(pair, [fs, fs], gc.label, T=args.T, form="packs", streams=(cs, ss),
+        T2 = max(4, args.T // 2)      # the variants beside config 4 proper run half as many iterations
+        ref = x["packs_form"]["t_comp_ms"] * T2 / args.T
+        x["packs_form_sharing_gemm_kernel"] = crossover_run(pair, [fs, fs], gc.label, T=T2, form="packs", streams=(cs, ss),
                                                             t_comp_reference=ref)
         x["packs_form_sharing_gemm_kernel_beside_preset"] = crossover_run(
-            pair, [fs, fs], gc.label, T=args.T, form="packs", tuning=beside, streams=(cs, ss), t_comp_reference=ref)
+            pair, [fs, fs], gc.label, T=T2, form="packs", tuning=beside, streams=(cs, ss), t_comp_reference=ref)
         alu, alu_label = alu_standin(x["packs_form"]["compute_alone_ms"][0])
-        x["alu_standin_packs_form"] = crossover_run(pair, [alu, alu], alu_label, T=args.T, form="packs", streams=(cs, ss))
+        x["alu_standin_packs_form"] = crossover_run(pair, [alu, alu], alu_label, T=T2, form="packs", streams=(cs, ss))
         # the row-per-wavefront copy kernels fill every wave slot of the chip by default; a compute
         # kernel of one long-lived workgroup per compute unit that is dispatched meanwhile lands
         # unevenly and stays so.  XS_PRESET_LEAVE_WAVE_SLOTS caps the copies at 10 per compute unit.
         x["alu_standin_packs_form_leave_wave_slots_preset"] = crossover_run(
-            pair, [alu, alu], alu_label, T=args.T, form="packs",
+            pair, [alu, alu], alu_label, T=T2, form="packs",
             tuning=xs.tuning_preset(xs.PRESET_LEAVE_WAVE_SLOTS), streams=(cs, ss))
-        x["alu_standin_gather_form"] = crossover_run(pair, [alu, alu], alu_label, T=args.T, form="gather", streams=(cs, ss))
+        x["alu_standin_gather_form"] = crossover_run(pair, [alu, alu], alu_label, T=T2, form="gather", streams=(cs, ss))
         # N = 3 tasks (Algorithm 1 is written for N): a second ResNet-50-shaped task joins
         third = harness.make_task(wl.RESNET50, "cuda")
-        x["n3_packs_form"] = crossover_run([resnet, vgg, third], [f0, f0, f0], gc.label, T=max(4, args.T // 2),
+        x["n3_packs_form"] = crossover_run([resnet, vgg, third], [f0, f0, f0], gc.label, T=max(4, T2 // 2),
                                            form="packs", streams=(cs, ss))
         x["n3_alu_standin_gather_form"] = crossover_run([resnet, vgg, third], [alu, alu, alu], alu_label,
-                                                        T=max(4, args.T // 2), form="gather", streams=(cs, ss))
+                                                        T=max(4, T2 // 2), form="gather", streams=(cs, ss))
         del third
         # every case against the computation with the library's own GEMM kernel (a slower GEMM
         # that shares its compute units must make up for its own slowness first)

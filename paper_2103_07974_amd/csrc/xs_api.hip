@@ -207,77 +207,83 @@ extern "C" int xs_plan_create(const uint64_t *numel, const uint64_t *offsets, ui
     if (offsets[0] != 0) return fail(XS_ERR_SIZE, "xs_plan_create: offsets[0] must be 0");
     if (n_tensors >= UINT32_MAX - 1) return fail(XS_ERR_SIZE, "xs_plan_create: too many tensors");
 
-    std::vector<uint32_t> prefix(n_tensors + 1, 0);
-    uint64_t chunks = 0;
-    for (uint32_t t = 0; t < n_tensors; ++t) {
-        if (offsets[t + 1] < offsets[t] || numel[t] > offsets[t + 1] - offsets[t])
-            return fail(XS_ERR_SIZE,
-                        "xs_plan_create: tensor %u (numel %llu at offset %llu) overruns the next offset %llu",
-                        t, (unsigned long long)numel[t], (unsigned long long)offsets[t],
-                        (unsigned long long)offsets[t + 1]);
-        if (offsets[t + 1] > (UINT64_MAX >> 4))
-            return fail(XS_ERR_SIZE, "xs_plan_create: bucket too large");
-        const uint64_t seg_bytes = (offsets[t + 1] - offsets[t]) * (uint64_t)es;
-        prefix[t] = (uint32_t)chunks;
-        chunks += (seg_bytes + kChunkBytes - 1) / kChunkBytes;
-        if (chunks > 0x7fffffffull) return fail(XS_ERR_SIZE, "xs_plan_create: bucket too large");
-    }
-    prefix[n_tensors] = (uint32_t)chunks;
-
-    xs_plan *p = new (std::nothrow) xs_plan();
-    if (!p) return fail(XS_ERR_NOMEM, "xs_plan_create: host allocation failed");
-    p->magic = XS_PLAN_MAGIC;
-    p->n_tensors = n_tensors;
-    p->dtype = dtype;
-    p->elem_size = (uint32_t)es;
-    p->bucket_elems = offsets[n_tensors];
-    p->n_chunks = (uint32_t)chunks;
-    p->dev_blob = nullptr;
-
-    // rows of kRowBytes of this dtype: which tensor's segment holds each row's first element
-    const uint64_t row_elems = kRowBytes / (uint64_t)es;
-    const uint64_t n_rows = (offsets[n_tensors] + row_elems - 1) / row_elems;
-    if (n_rows > 0x7fffffffull) { delete p; return fail(XS_ERR_SIZE, "xs_plan_create: bucket too large"); }
-    p->n_rows = n_rows;
-    std::vector<uint32_t> row_first((size_t)n_rows, 0);
-    {
-        uint32_t t = 0;
-        for (uint64_t r = 0; r < n_rows; ++r) {
-            const uint64_t j = r * row_elems;
-            while (t + 1 < n_tensors && offsets[t + 1] <= j) ++t;
-            row_first[(size_t)r] = t;
+    xs_plan *p = nullptr;
+    try {
+        std::vector<uint32_t> prefix(n_tensors + 1, 0);
+        uint64_t chunks = 0;
+        for (uint32_t t = 0; t < n_tensors; ++t) {
+            if (offsets[t + 1] < offsets[t] || numel[t] > offsets[t + 1] - offsets[t])
+                return fail(XS_ERR_SIZE,
+                            "xs_plan_create: tensor %u (numel %llu at offset %llu) overruns the next offset %llu",
+                            t, (unsigned long long)numel[t], (unsigned long long)offsets[t],
+                            (unsigned long long)offsets[t + 1]);
+            if (offsets[t + 1] > (UINT64_MAX >> 4))
+                return fail(XS_ERR_SIZE, "xs_plan_create: bucket too large");
+            const uint64_t seg_bytes = (offsets[t + 1] - offsets[t]) * (uint64_t)es;
+            prefix[t] = (uint32_t)chunks;
+            chunks += (seg_bytes + kChunkBytes - 1) / kChunkBytes;
+            if (chunks > 0x7fffffffull) return fail(XS_ERR_SIZE, "xs_plan_create: bucket too large");
         }
-    }
+        prefix[n_tensors] = (uint32_t)chunks;
 
-    // one device blob: offsets | numel | chunk_prefix | row_first
-    const size_t off_bytes = (size_t)(n_tensors + 1) * 8;
-    const size_t num_bytes = (size_t)n_tensors * 8;
-    const size_t pre_bytes = (size_t)(n_tensors + 1) * 4;
-    const size_t row_bytes = (size_t)n_rows * 4;
-    std::vector<unsigned char> host(off_bytes + num_bytes + pre_bytes + row_bytes);
-    memcpy(host.data(), offsets, off_bytes);
-    if (n_tensors) memcpy(host.data() + off_bytes, numel, num_bytes);
-    memcpy(host.data() + off_bytes + num_bytes, prefix.data(), pre_bytes);
-    if (n_rows) memcpy(host.data() + off_bytes + num_bytes + pre_bytes, row_first.data(), row_bytes);
-    hipError_t e = hipMalloc(&p->dev_blob, host.size());
-    if (e != hipSuccess) {
+        p = new (std::nothrow) xs_plan();
+        if (!p) return fail(XS_ERR_NOMEM, "xs_plan_create: host allocation failed");
+        p->magic = XS_PLAN_MAGIC;
+        p->n_tensors = n_tensors;
+        p->dtype = dtype;
+        p->elem_size = (uint32_t)es;
+        p->bucket_elems = offsets[n_tensors];
+        p->n_chunks = (uint32_t)chunks;
+        p->dev_blob = nullptr;
+
+        // rows of kRowBytes of this dtype: which tensor's segment holds each row's first element
+        const uint64_t row_elems = kRowBytes / (uint64_t)es;
+        const uint64_t n_rows = (offsets[n_tensors] + row_elems - 1) / row_elems;
+        if (n_rows > 0x7fffffffull) { delete p; return fail(XS_ERR_SIZE, "xs_plan_create: bucket too large"); }
+        p->n_rows = n_rows;
+        std::vector<uint32_t> row_first((size_t)n_rows, 0);
+        {
+            uint32_t t = 0;
+            for (uint64_t r = 0; r < n_rows; ++r) {
+                const uint64_t j = r * row_elems;
+                while (t + 1 < n_tensors && offsets[t + 1] <= j) ++t;
+                row_first[(size_t)r] = t;
+            }
+        }
+
+        // one device blob: offsets | numel | chunk_prefix | row_first
+        const size_t off_bytes = (size_t)(n_tensors + 1) * 8;
+        const size_t num_bytes = (size_t)n_tensors * 8;
+        const size_t pre_bytes = (size_t)(n_tensors + 1) * 4;
+        const size_t row_bytes = (size_t)n_rows * 4;
+        std::vector<unsigned char> host(off_bytes + num_bytes + pre_bytes + row_bytes);
+        memcpy(host.data(), offsets, off_bytes);
+        if (n_tensors) memcpy(host.data() + off_bytes, numel, num_bytes);
+        memcpy(host.data() + off_bytes + num_bytes, prefix.data(), pre_bytes);
+        if (n_rows) memcpy(host.data() + off_bytes + num_bytes + pre_bytes, row_first.data(), row_bytes);
+        hipError_t e = hipMalloc(&p->dev_blob, host.size());
+        if (e != hipSuccess) {
+            delete p;
+            fail_hip(e, "hipMalloc(plan tables)");
+            return e == hipErrorOutOfMemory ? XS_ERR_NOMEM : XS_ERR_HIP;
+        }
+        e = hipMemcpy(p->dev_blob, host.data(), host.size(), hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            (void)hipFree(p->dev_blob);
+            delete p;
+            return fail_hip(e, "hipMemcpy(plan tables)");
+        }
+        unsigned char *d = (unsigned char *)p->dev_blob;
+        p->tables.offsets = (const uint64_t *)d;
+        p->tables.numel = (const uint64_t *)(d + off_bytes);
+        p->tables.chunk_prefix = (const uint32_t *)(d + off_bytes + num_bytes);
+        p->tables.row_first = (const uint32_t *)(d + off_bytes + num_bytes + pre_bytes);
+        *out = p;
+        return XS_OK;
+    } catch (const std::bad_alloc &) {      // the host-side tables (one word per KiB of bucket)
         delete p;
-        fail_hip(e, "hipMalloc(plan tables)");
-        return e == hipErrorOutOfMemory ? XS_ERR_NOMEM : XS_ERR_HIP;
+        return fail(XS_ERR_NOMEM, "xs_plan_create: host allocation failed");
     }
-    e = hipMemcpy(p->dev_blob, host.data(), host.size(), hipMemcpyHostToDevice);
-    if (e != hipSuccess) {
-        (void)hipFree(p->dev_blob);
-        delete p;
-        return fail_hip(e, "hipMemcpy(plan tables)");
-    }
-    unsigned char *d = (unsigned char *)p->dev_blob;
-    p->tables.offsets = (const uint64_t *)d;
-    p->tables.numel = (const uint64_t *)(d + off_bytes);
-    p->tables.chunk_prefix = (const uint32_t *)(d + off_bytes + num_bytes);
-    p->tables.row_first = (const uint32_t *)(d + off_bytes + num_bytes + pre_bytes);
-    *out = p;
-    return XS_OK;
 }
 
 extern "C" int xs_plan_destroy(xs_plan *plan)

@@ -103,8 +103,13 @@ extern "C" int xs_app_create(const xs_app_desc *d, xs_app **out)
     a->pplan = d->parameter_plan;
     a->W = d->W;
     if (!empty && !gather) {
-        a->grad_tables.assign(d->grad_tensor_ptrs, d->grad_tensor_ptrs + d->W);
-        a->buckets.assign(d->replica_buckets, d->replica_buckets + d->W);
+        try {
+            a->grad_tables.assign(d->grad_tensor_ptrs, d->grad_tensor_ptrs + d->W);
+            a->buckets.assign(d->replica_buckets, d->replica_buckets + d->W);
+        } catch (const std::bad_alloc &) {
+            delete a;
+            return fail(XS_ERR_NOMEM, "xs_app_create: host allocation failed");
+        }
     }
     a->gather_table = d->grad_ptrs_tw;
     a->flags = d->flags;

@@ -5,7 +5,9 @@
 // allocates.  Here the same tables live in one fixed device array of the library, `scratch`,
 // and are rewritten on the caller's stream in front of every pack by small kernels that
 // receive the table entries through their kernel arguments (no host-to-device copy, no
-// allocation, nothing that a capture could not record).  The pack itself is the same kernel.
+// allocation, nothing that a capture could not record).  The pack itself is the chunk-form
+// copy kernel of xs_copy.hip, whose tables are O(tensors) and fit the array; the result is
+// bit-identical to xs_fuse_pack's.
 //
 // Every call on a GPU shares that GPU's array: the array keeps the last call's tables, each
 // call overwrites the part it uses, and two calls that overlap in time on one GPU (different
