@@ -414,7 +414,11 @@ int launch_reduce_sgd(const Tuning &tn, const void *const *replicas, uint32_t W,
     // 20 loads per lane); more wavefronts than that only disorder the DRAM access stream,
     // fewer expose the latency of the kernel's prologue.  The LDS reservation (unused by the
     // kernel) is what caps the residency.
-    const int lds_auto = 16384;
+    // The instances that look the row's tensor up (per-tensor records, unpack fused in) behave
+    // differently at W = 16 half-precision replicas (20 KiB in flight per wavefront): five per
+    // compute unit (28 KiB) is their optimum, +3 to +6 % over ten; at four they fall off again.
+    const bool looks_up = l.a.thp.rec != nullptr || l.a.param_ptrs != nullptr;
+    const int lds_auto = (half && W == 16 && looks_up) ? 28672 : 16384;
     l.lds_reserve = (unsigned)(tn.reduce_lds_reserve() < 0 ? lds_auto : tn.reduce_lds_reserve());
     const bool ntg = tn.nt_grads(), nts = tn.nt_state();
 
