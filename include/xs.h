@@ -351,7 +351,9 @@ int xs_tuning_get(int key, int *value_out);
  *                             reduce kernels keep that much room by default.  For a task whose
  *                             neighbour launches few long-lived workgroups: dispatched while
  *                             copies fill every wave slot they land on whichever compute
- *                             units have room first and stay unevenly spread
+ *                             units have room first and stay unevenly spread.  Beside kernels
+ *                             that own whole compute units (GEMM macro-tiles) the slower copies
+ *                             only hold the compute units longer: use the defaults there
  * XS_ERR_INVALID_ARG for an unknown preset or a NULL pointer.
  */
 typedef enum { XS_PRESET_ALONE = 0, XS_PRESET_BESIDE_COMPUTE = 1, XS_PRESET_LEAVE_WAVE_SLOTS = 2 } xs_tuning_preset_id;
