@@ -690,7 +690,7 @@ def cpu_baseline(w, budget_s=8.0):
 
 
 # --------------------------------------------------------------------------- profiling modes
-def kernels_only(name, launches):
+def kernels_only(name, launches, pooled=True):
     """Stand-alone launches of every kernel of one workload and nothing else, for
     `rocprofv3 --kernel-trace --stats`: each kernel's average is then its stand-alone time."""
     import torch
@@ -698,7 +698,7 @@ def kernels_only(name, launches):
     xs.lib(); torch.cuda.set_device(0)
     w = wl.WORKLOADS[name]
     n_sets = 3 if name == "resnet50" else 1
-    tasks = [harness.make_task(w, "cuda") for _ in range(n_sets)]
+    tasks = [harness.make_task(w, "cuda", pooled=pooled) for _ in range(n_sets)]
     for t in tasks:
         t.momentum.copy_(wl.make_flat(t.n_bucket, 0.01, w.seed + 77, device="cuda"))
     torch.cuda.synchronize()
@@ -731,7 +731,7 @@ def kernels_only(name, launches):
     return 0
 
 
-def traffic_probe(name):
+def traffic_probe(name, pooled=True):
     """A few launches for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`, one workload per
     process: a plain device copy of known size first (its counter reading calibrates the
     unit), then every kernel of the path.  Nothing is freed while the counters are collected
@@ -752,7 +752,7 @@ def traffic_probe(name):
     w = wl.WORKLOADS[name]
     # the largest set: all workers' tensor lists point at worker 0's tensors (the buckets stay
     # distinct), which keeps the number of set-up launches under the counters small
-    task = harness.make_task(w, "cuda", shared_grads=name == "bert_large_f16")
+    task = harness.make_task(w, "cuda", shared_grads=name == "bert_large_f16", pooled=pooled)
     for _ in range(3):
         xs.fuse_pack(task.gplan, task.grad_tables[0], task.buckets[0])
         xs.fuse_pack_many(task.gplan, task.grad_tables, task.buckets)
@@ -777,13 +777,16 @@ def stream_ceiling():
     """Attainable HBM rate of plain streaming kernels with the access mix of pack/unpack (1:1
     copy) and of the fused reduce + SGD at W = 8 (10 streams read, 2 written): one-wavefront
     workgroups in address order, one 16-byte vector per lane, non-temporal accesses, random
-    data, for several occupancy caps (LDS reserved per workgroup)."""
+    data, buffers of the VGG-16 bucket's size carved from one allocation as the harness lays a
+    task out, for several occupancy caps (LDS reserved per workgroup)."""
     import torch
     import bench_standin as bs
     bs.lib(); torch.cuda.set_device(0)
     s = torch.cuda.Stream()
-    n = 128 * 1024 * 1024                      # 512 MiB per buffer
-    bufs = [torch.empty(n, dtype=torch.float32, device="cuda").normal_(0, 1e-3) for _ in range(12)]
+    from paper_2103_07974_amd import xs
+    n = 138357568                              # elements per buffer: the VGG-16-shaped bucket
+    bufs = [b.normal_(0, 1e-3) for b in xs.pool_alloc([(n, torch.float32)] * 12)]   # one allocation, as the
+                                                                                   # harness lays a task out
     for lds in (0, 8192, 16384, 32768):
         ms = _median(timed_launches(lambda i: bs.copy(bufs[i % 5], bufs[5 + i % 5], lds, s), s, 30, 5))
         print(json.dumps({"kernel": "copy 1 read : 1 write", "lds_reserve": lds, "ms": ms, "GBs": 2 * n * 4 / ms / 1e6}), flush=True)
@@ -851,6 +854,9 @@ def main():
     ap.add_argument("--kernels-only", metavar="WORKLOAD", help="resnet50 | vgg16 | bert_large_f16")
     ap.add_argument("--launches", type=int, default=60)
     ap.add_argument("--traffic-probe", metavar="WORKLOAD", help="resnet50 | vgg16 | bert_large_f16")
+    ap.add_argument("--separate-allocations", action="store_true",
+                    help="with --traffic-probe / --kernels-only: every bucket, parameters and momentum in an "
+                         "allocation of their own instead of one pool")
     ap.add_argument("--stream-ceiling", action="store_true")
     ap.add_argument("--power", action="store_true")
     ap.add_argument("--footprint", action="store_true")
@@ -878,9 +884,9 @@ def main():
     if args.crossover_case:
         return crossover_case(json.loads(args.crossover_case))
     if args.kernels_only:
-        return kernels_only(args.kernels_only, args.launches)
+        return kernels_only(args.kernels_only, args.launches, not args.separate_allocations)
     if args.traffic_probe:
-        return traffic_probe(args.traffic_probe)
+        return traffic_probe(args.traffic_probe, not args.separate_allocations)
     if args.stream_ceiling:
         return stream_ceiling()
     if args.power:

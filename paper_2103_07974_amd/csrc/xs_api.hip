@@ -185,6 +185,23 @@ extern "C" int xs_bucket_layout(const uint64_t *numel, uint32_t n_tensors, uint6
     return XS_OK;
 }
 
+// One allocation for a task's flat buffers, each at a multiple of XS_POOL_ALIGN.
+extern "C" int xs_pool_layout(const uint64_t *nbytes, uint32_t n_buffers, uint64_t *offsets_out)
+{
+    if (!offsets_out) return fail(XS_ERR_INVALID_ARG, "xs_pool_layout: offsets_out is NULL");
+    if (n_buffers > 0 && !nbytes) return fail(XS_ERR_INVALID_ARG, "xs_pool_layout: nbytes is NULL");
+    const uint64_t a = XS_POOL_ALIGN;
+    uint64_t pos = 0;
+    offsets_out[0] = 0;
+    for (uint32_t i = 0; i < n_buffers; ++i) {
+        if (nbytes[i] > UINT64_MAX - pos - a)
+            return fail(XS_ERR_SIZE, "xs_pool_layout: pool size overflows 64 bits");
+        pos = (pos + nbytes[i] + a - 1) / a * a;
+        offsets_out[i + 1] = pos;
+    }
+    return XS_OK;
+}
+
 static int elem_size_of(int dtype)
 {
     switch (dtype) {

@@ -51,7 +51,7 @@ PRESET_BESIDE_COMPUTE = 1
 PRESET_LEAVE_WAVE_SLOTS = 2
 
 EXPORTS = [
-    "xs_status_string", "xs_last_error", "xs_bucket_layout", "xs_plan_create", "xs_plan_destroy",
+    "xs_status_string", "xs_last_error", "xs_bucket_layout", "xs_pool_layout", "xs_plan_create", "xs_plan_destroy",
     "xs_plan_bucket_elems", "xs_plan_n_tensors", "xs_fuse_pack", "xs_fuse_pack_many", "xs_fuse_pack_static",
     "xs_fuse_unpack",
     "xs_fused_reduce_sgd", "xs_fused_reduce_sgd_mp", "xs_fused_gather_reduce_sgd",
@@ -116,6 +116,7 @@ def lib() -> ctypes.CDLL:
     L.xs_status_string.argtypes = [ctypes.c_int]; L.xs_status_string.restype = ctypes.c_char_p
     L.xs_last_error.argtypes = []; L.xs_last_error.restype = ctypes.c_char_p
     L.xs_bucket_layout.argtypes = [u64p, ctypes.c_uint32, ctypes.c_uint64, u64p]
+    L.xs_pool_layout.argtypes = [u64p, ctypes.c_uint32, u64p]
     L.xs_plan_create.argtypes = [u64p, u64p, ctypes.c_uint32, ctypes.c_int, ctypes.POINTER(vp)]
     L.xs_plan_destroy.argtypes = [vp]
     L.xs_plan_bucket_elems.argtypes = [vp]; L.xs_plan_bucket_elems.restype = ctypes.c_uint64
@@ -207,6 +208,28 @@ def bucket_layout(numel: Sequence[int], align_elems: int = 1) -> List[int]:
     out = (ctypes.c_uint64 * (n + 1))()
     _check(lib().xs_bucket_layout(a, n, int(align_elems), out), "xs_bucket_layout")
     return list(out)
+
+
+POOL_ALIGN = 2 << 20
+
+
+def pool_layout(nbytes: Sequence[int]) -> List[int]:
+    """Byte offsets of a task's flat buffers inside one allocation (xs_pool_layout); the last
+    entry is the size needed behind a POOL_ALIGN-aligned base."""
+    n = len(nbytes)
+    a = (ctypes.c_uint64 * max(n, 1))(*nbytes)
+    out = (ctypes.c_uint64 * (n + 1))()
+    _check(lib().xs_pool_layout(a, n, out), "xs_pool_layout")
+    return list(out)
+
+
+def pool_alloc(sizes: Sequence[tuple], device="cuda") -> List["torch.Tensor"]:
+    """One device allocation carved into flat tensors: sizes = [(n_elems, dtype), ...]."""
+    nbytes = [int(n) * torch.empty(0, dtype=dt).element_size() for n, dt in sizes]
+    offs = pool_layout(nbytes)
+    pool = torch.empty(offs[-1] + POOL_ALIGN, dtype=torch.uint8, device=device)
+    base = (-pool.data_ptr()) % POOL_ALIGN
+    return [pool[base + offs[i]: base + offs[i] + nbytes[i]].view(dt) for i, (n, dt) in enumerate(sizes)]
 
 
 class Plan:

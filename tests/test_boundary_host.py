@@ -161,6 +161,20 @@ def test_mixed_precision_option_validation():
     assert rc == xs.XS_ERR_UNSUPPORTED and "model_copy" in xs.last_error()
 
 
+def test_pool_layout():
+    sizes = [1, 2 << 20, (2 << 20) + 1, 0, 553430272]
+    offs = xs.pool_layout(sizes)
+    assert offs[0] == 0 and len(offs) == len(sizes) + 1
+    for i, n in enumerate(sizes):
+        assert offs[i] % xs.POOL_ALIGN == 0 and offs[i + 1] >= offs[i] + n and offs[i + 1] - offs[i] < n + xs.POOL_ALIGN + 1
+    assert offs[-1] == sum((n + xs.POOL_ALIGN - 1) // xs.POOL_ALIGN * xs.POOL_ALIGN for n in sizes)
+    assert xs.pool_layout([]) == [0]
+    L = xs.lib()
+    assert L.xs_pool_layout(None, 0, None) == xs.XS_ERR_INVALID_ARG
+    big = (ctypes.c_uint64 * 2)(2 ** 63, 2 ** 63); out = (ctypes.c_uint64 * 3)()
+    assert L.xs_pool_layout(big, 2, out) == xs.XS_ERR_SIZE
+
+
 def test_launch_settings_presets_and_atomics():
     L = xs.lib()
     alone, beside = xs.tuning_preset(xs.PRESET_ALONE), xs.tuning_preset(xs.PRESET_BESIDE_COMPUTE)
