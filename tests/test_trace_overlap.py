@@ -49,6 +49,22 @@ def test_gemm_time_lost_beside_sync(tmp_path):
     assert abs(r["sync_busy_time_ms"] - 1.9) < 1e-9
 
 
+def test_gemm_time_lost_is_summed_over_kernel_names(tmp_path):
+    a, b, c = "Cijk_small_tile", "Cijk_large_tile", "Cijk_never_beside"
+    sync = "void xs::gather_reduce_sgd_kernel<4>(...)"
+    rows = [(a, 0, 100_000), (a, 100_000, 200_000), (b, 200_000, 500_000), (c, 500_000, 900_000),   # alone
+            (a, 1_000_000, 1_150_000),                      # beside: +0.05 ms over its own 0.1 ms
+            (b, 1_150_000, 1_850_000),                      # beside: +0.4 ms over its own 0.3 ms
+            (sync, 1_010_000, 1_800_000)]
+    p = tmp_path / "t_kernel_trace.csv"
+    _write(p, rows)
+    r = trace_overlap.analyse(str(p))
+    assert abs(r["gemm_time_lost_beside_sync_ms"] - 0.45) < 1e-9
+    assert r["gemm_kernel_with_most_time_beside_sync"] == b
+    assert r["gemm_kernels_alone"] == 1 and r["gemm_kernels_beside_sync"] == 1
+    assert abs(r["gemm_median_alone_us"] - 300.0) < 1e-9 and abs(r["gemm_median_beside_sync_us"] - 700.0) < 1e-9
+
+
 def test_merge_and_classify():
     assert trace_overlap.merge([(5, 7), (0, 3), (2, 4), (7, 9)]) == [(0, 4), (5, 9)]
     assert trace_overlap.classify("void xs::copy_kernel<false>(...)") == "sync"

@@ -10,8 +10,8 @@ with Cijk_) and the arithmetic-only stand-in of bench_standin.hip count as compu
 Only the part of the trace where both kinds appear within one millisecond of each other is
 used, so that stand-alone timing loops in the same trace do not dilute the figure.
 It also reports what the overlap costs the computation: the GEMM kernels that ran while a
-sync kernel was running against the median of those that ran alone (time lost), beside the
-time the sync stream was busy.
+sync kernel was running against the median of those of the same name that ran alone (time
+lost, summed over the kernel names), beside the time the sync stream was busy.
 """
 from __future__ import annotations
 
@@ -66,25 +66,35 @@ def analyse(path: str, slack_ns: int = 1_000_000):
     used = [iv for iv in sync if overlap_with(iv, near) > 0]
     tot = sum(e - s for s, e in used)
     inside = sum(overlap_with(iv, comp_m) for iv in used)
-    # what the overlap costs the computation: GEMM kernels (one size per trace) that ran while
-    # a sync kernel was running, against the median duration of those that ran alone
+    # what the overlap costs the computation: per GEMM kernel name, the launches that ran while
+    # a sync kernel was running against the median duration of those of that name that ran
+    # alone (a trace may also hold the timing runs of other hipBLASLt algorithms: names with no
+    # launch beside a sync kernel are left out); the "main" kernel is the name with the most
+    # time beside sync kernels
     sync_m = merge(used)
-    # (only the GEMM kernel that shares the crossover phase: a trace may also hold the timing
-    # runs of other hipBLASLt algorithms)
-    names = [nm for iv, nm in comp_named if nm.startswith("Cijk_") and overlap_with(iv, sync_m) > 0]
-    main = max(set(names), key=names.count) if names else None
-    gemm = [iv for iv, nm in comp_named if nm == main]
-    alone = sorted(e - s for s, e in gemm if overlap_with((s, e), sync_m) == 0)
-    beside = [e - s for s, e in gemm if overlap_with((s, e), sync_m) > 0]
+    by_name = {}
+    for iv, nm in comp_named:
+        if nm.startswith("Cijk_"):
+            by_name.setdefault(nm, ([], []))[1 if overlap_with(iv, sync_m) > 0 else 0].append(iv[1] - iv[0])
+    lost, main, main_time = None, None, -1
+    for nm, (alone_d, beside_d) in by_name.items():
+        if not beside_d:
+            continue
+        if alone_d:
+            base_nm = sorted(alone_d)[len(alone_d) // 2]
+            lost = (lost or 0) + sum(d - base_nm for d in beside_d)
+        if sum(beside_d) > main_time:
+            main, main_time = nm, sum(beside_d)
+    alone, beside = (sorted(by_name[main][0]), by_name[main][1]) if main else ([], [])
     base = alone[len(alone) // 2] if alone else None
-    stretch = sum(d - base for d in beside) if base is not None else None
     return {"sync_kernels_in_crossover_phase": len(used), "sync_kernels_total": len(sync),
             "sync_time_ms": tot / 1e6, "sync_time_inside_compute_ms": inside / 1e6,
             "stream_overlap_fraction": inside / tot if tot else None,
             "gemm_kernels_alone": len(alone), "gemm_median_alone_us": base / 1e3 if base else None,
             "gemm_kernels_beside_sync": len(beside),
             "gemm_median_beside_sync_us": sorted(beside)[len(beside) // 2] / 1e3 if beside else None,
-            "gemm_time_lost_beside_sync_ms": stretch / 1e6 if stretch is not None else None,
+            "gemm_kernel_with_most_time_beside_sync": main[:60] if main else None,
+            "gemm_time_lost_beside_sync_ms": lost / 1e6 if lost is not None else None,
             "sync_busy_time_ms": sum(e - s for s, e in sync_m) / 1e6}
 
 
