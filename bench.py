@@ -320,9 +320,19 @@ def crossover_run(tasks, computes, label, T=20, rounds=5, form="packs", tuning=N
     import torch
     from paper_2103_07974_amd import xs
     kw = {"fused_gather": form == "gather", "fused_unpack": form == "fused_unpack"}
-    apps = [t.make_app(c, tuning=tuning, **kw) for t, c in zip(tasks, computes)]
-    alone = apps if tuning is None else [t.make_app(c, **kw) for t, c in zip(tasks, computes)]
     cs, ss = streams if streams is not None else (torch.cuda.Stream(), torch.cuda.Stream())
+    spans = None        # while a list: (task, start event, end event) of every computation on the compute stream
+
+    def timed(i, c):
+        def compute(stream_ptr):
+            if spans is None or stream_ptr != cs.cuda_stream:
+                return c(stream_ptr)
+            e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+            e0.record(cs); c(stream_ptr); e1.record(cs)
+            spans.append((i, e0, e1))
+        return compute
+    apps = [t.make_app(timed(i, c), tuning=tuning, **kw) for i, (t, c) in enumerate(zip(tasks, computes))]
+    alone = apps if tuning is None else [t.make_app(c, **kw) for t, c in zip(tasks, computes)]
     N = len(apps)
 
     def run_cross(record=None):
@@ -413,6 +423,26 @@ def crossover_run(tasks, computes, label, T=20, rounds=5, form="packs", tuning=N
         res["t_comp_unrestricted_ms"] = t_comp_reference
         res["hidden_fraction_vs_unrestricted_compute"] = \
             1.0 - (t_cross - t_comp_reference) / (t_serial - t_comp)
+    if N == 2:
+        # Per task (two tasks): what task i's synchronisations cost the schedule = how much
+        # longer the other task's computations were while they ran beside them, plus how long
+        # task i's own next computation had to wait (the gap in front of it on the compute
+        # stream); hidden_i = 1 - cost_i / (number of overlapped synchronisations * M_i alone).
+        spans = []
+        run_cross()
+        sp, spans = spans, None
+        cost = [0.0, 0.0]
+        n_sync = [0, 0]
+        for k in range(1, len(sp)):                 # every computation but the first runs beside the
+            i, e0, e1 = sp[k]                       # synchronisation of the task that computed before it
+            other = 1 - i
+            n_sync[other] += 1
+            cost[other] += max(0.0, e0.elapsed_time(e1) - comp_alone[i])       # beside task `other`'s sync
+            cost[i] += max(0.0, sp[k - 1][2].elapsed_time(e0))                   # waiting for its own sync
+        res["per_task"] = [{"sync_alone_ms": sync_alone[i], "synchronisations_counted": n_sync[i],
+                            "cost_to_the_schedule_ms": cost[i],
+                            "hidden_fraction": 1.0 - cost[i] / (n_sync[i] * sync_alone[i]) if n_sync[i] else None}
+                           for i in range(2)]
     for a in set(apps + alone):
         a.destroy()
     return res
@@ -1080,6 +1110,7 @@ def main():
             "target": 0.90,
             "target_met": bool(c["end_to_end_hidden_fraction"] is not None and c["end_to_end_hidden_fraction"] >= 0.90),
             "speedup_vs_serial": c["speedup_vs_serial"],
+            "per_task": {"A_resnet50": c["per_task"][0], "B_vgg16": c["per_task"][1]},
             "best_of_the_library_s_forms_and_settings": {"which": best_key, "end_to_end_hidden_fraction": strict(best_key)},
             "why": "the bf16 GEMM chain alone runs at the board's 1400 W power limit and its kernel owns every "
                    "compute unit whole; the HBM-bound synchronisation kernels draw 1.0-1.2 kW themselves, so what "
