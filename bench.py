@@ -872,6 +872,33 @@ def few_cu_sweep():
     return 0
 
 
+def ratio_sweep():
+    """Section 1, first contribution: the synchronisation delay disappears while comm/comp < 1.
+    The pair of config 4 (ResNet-50- and VGG-16-shaped synchronisations, gathering form) beside
+    an arithmetic-only computation of varied length, i.e. at varied comm/comp ratio, against
+    the timeline model of Algorithm 1 for two tasks: one outer iteration lasts
+    max(C_A, M_B) + max(C_B, M_A)."""
+    import torch
+    import bench_standin as bs
+    from paper_2103_07974_amd import harness, workloads as wl, xs
+    xs.lib(); bs.lib(); torch.cuda.set_device(0); torch.zeros(1, device="cuda")
+    pair = [harness.make_task(wl.RESNET50, "cuda"), harness.make_task(wl.VGG16, "cuda")]
+    cs, ss = torch.cuda.Stream(), torch.cuda.Stream()
+    for target_ms in (0.3, 0.6, 0.9, 1.2, 1.8, 2.4, 4.8, 9.6):
+        alu, label = alu_standin(target_ms)
+        r = crossover_run(pair, [alu, alu], label, T=20, rounds=3, form="gather", streams=(cs, ss))
+        C, M = r["compute_alone_ms"], r["sync_alone_ms"]
+        model_extra = max(0.0, M[1] - C[0]) + max(0.0, M[0] - C[1])        # per outer iteration
+        print(json.dumps({
+            "compute_ms": C, "sync_alone_ms": M, "comm_comp_ratio_task_B": M[1] / C[0], "comm_comp_ratio_task_A": M[0] / C[1],
+            "hidden_fraction_measured": r["end_to_end_hidden_fraction"],
+            "hidden_fraction_timeline_model": 1.0 - model_extra / (M[0] + M[1]),
+            "t_comp_ms": r["t_comp_ms"], "t_serial_ms": r["t_serial_ms"], "t_cross_ms": r["t_cross_ms"],
+            "t_cross_timeline_model_ms": r["T"] * (max(C[0], M[1]) + max(C[1], M[0])) + M[1],
+            "per_task_hidden": [p["hidden_fraction"] for p in r.get("per_task", [])]}), flush=True)
+    return 0
+
+
 # --------------------------------------------------------------------------- main
 def main():
     ap = argparse.ArgumentParser()
@@ -891,6 +918,7 @@ def main():
     ap.add_argument("--power", action="store_true")
     ap.add_argument("--footprint", action="store_true")
     ap.add_argument("--few-cu-sweep", action="store_true")
+    ap.add_argument("--ratio-sweep", action="store_true")
     ap.add_argument("--crossover-sweep", action="store_true")
     ap.add_argument("--crossover-case", metavar="JSON")
     ap.add_argument("--crossover-only", action="store_true",
@@ -925,6 +953,8 @@ def main():
         return footprint_probe()
     if args.few_cu_sweep:
         return few_cu_sweep()
+    if args.ratio_sweep:
+        return ratio_sweep()
 
     import torch
     import bench_standin as bs
