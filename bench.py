@@ -817,11 +817,14 @@ def stream_ceiling():
     n = 138357568                              # elements per buffer: the VGG-16-shaped bucket
     bufs = [b.normal_(0, 1e-3) for b in xs.pool_alloc([(n, torch.float32)] * 12)]   # one allocation, as the
                                                                                    # harness lays a task out
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
     for lds in (0, 8192, 16384, 32768):
         ms = _median(timed_launches(lambda i: bs.copy(bufs[i % 5], bufs[5 + i % 5], lds, s), s, 30, 5))
         print(json.dumps({"kernel": "copy 1 read : 1 write", "lds_reserve": lds, "ms": ms, "GBs": 2 * n * 4 / ms / 1e6}), flush=True)
         ms = _median(timed_launches(lambda i: bs.mix(bufs[:10], bufs[10], bufs[11], lds, s), s, 30, 5))
         print(json.dumps({"kernel": "10 reads : 2 writes", "lds_reserve": lds, "ms": ms, "GBs": 12 * n * 4 / ms / 1e6}), flush=True)
+        ms = _median(timed_launches(lambda i: bs.read(bufs[:10], sink, lds, s), s, 30, 5))
+        print(json.dumps({"kernel": "10 reads, no write", "lds_reserve": lds, "ms": ms, "GBs": 10 * n * 4 / ms / 1e6}), flush=True)
     return 0
 
 

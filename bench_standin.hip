@@ -10,7 +10,7 @@
 //   bs_alu           an arithmetic-only kernel of ordinary occupancy and no memory traffic
 //   bs_stream_*      streams restricted to a set of compute units (hipExtStreamCreateWithCUMask)
 //   bs_census        which compute units the workgroups of a stream actually land on
-//   bs_copy / bs_mix plain streaming kernels (1:1 copy; 10 reads : 2 writes) that give the
+//   bs_copy / bs_mix / bs_read  plain streaming kernels (1:1 copy; 10 reads : 2 writes; 10 reads) that give the
 //                    chip's attainable HBM rate for the access mix of pack/unpack and of the
 //                    fused reduce + SGD, beside which the library's kernels are reported
 #include <hip/hip_runtime.h>
@@ -126,6 +126,21 @@ __global__ __launch_bounds__(64) void mix_kernel(Mix10 m, f32x4 *o0, f32x4 *o1, 
     __builtin_nontemporal_store(s + g[9], o1 + i);
 }
 
+// 10 streams read, nothing written (a wavefront that finds an all-ones sum, which random data
+// never gives, writes one word, so that the loads cannot be dropped): the read-only limit
+__global__ __launch_bounds__(64) void read_kernel(Mix10 m, uint32_t *sink, uint64_t nvec)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * 64 + threadIdx.x;
+    if (i >= nvec) return;
+    f32x4 g[10];
+#pragma unroll
+    for (int k = 0; k < 10; ++k) g[k] = __builtin_nontemporal_load(m.r[k] + i);
+    f32x4 s = g[0];
+#pragma unroll
+    for (int k = 1; k < 10; ++k) s = s + g[k];
+    if (__float_as_uint(s[0]) == 0xffffffffu && __float_as_uint(s[3]) == 0xffffffffu) sink[0] = 1u;
+}
+
 struct Gemm {
     hipblasLtHandle_t lt = nullptr;
     hipblasLtMatmulDesc_t desc = nullptr;
@@ -232,6 +247,24 @@ extern "C" int bs_mix(const void *const *reads, void *out0, void *out1, uint64_t
     if (blocks > 0x7fffffffull) return fail("bs_mix: too large");
     hipLaunchKernelGGL(mix_kernel, dim3((unsigned)blocks), dim3(64), lds_reserve, (hipStream_t)stream, m,
                        (f32x4 *)out0, (f32x4 *)out1, nvec);
+    BS_HIP(hipGetLastError());
+    return 0;
+}
+
+// reads: host array of 10 device pointers; every buffer `bytes` long; sink: one device word
+extern "C" int bs_read(const void *const *reads, void *sink, uint64_t bytes, uint32_t lds_reserve, void *stream)
+{
+    if (!reads || !sink || (bytes & 15u) || lds_reserve > 160 * 1024) return fail("bs_read: bad argument");
+    Mix10 m;
+    for (int k = 0; k < 10; ++k) {
+        if (!reads[k]) return fail("bs_read: reads[%d] is NULL", k);
+        m.r[k] = (const f32x4 *)reads[k];
+    }
+    const uint64_t nvec = bytes / 16, blocks = (nvec + 63) / 64;
+    if (blocks == 0) return 0;
+    if (blocks > 0x7fffffffull) return fail("bs_read: too large");
+    hipLaunchKernelGGL(read_kernel, dim3((unsigned)blocks), dim3(64), lds_reserve, (hipStream_t)stream, m,
+                       (uint32_t *)sink, nvec);
     BS_HIP(hipGetLastError());
     return 0;
 }

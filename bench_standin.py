@@ -47,6 +47,7 @@ def lib() -> ctypes.CDLL:
     L.bs_stream_destroy.argtypes = [vp]
     L.bs_copy.argtypes = [vp, vp, ctypes.c_uint64, ctypes.c_uint32, vp]
     L.bs_mix.argtypes = [ctypes.POINTER(vp), vp, vp, ctypes.c_uint64, ctypes.c_uint32, vp]
+    L.bs_read.argtypes = [ctypes.POINTER(vp), vp, ctypes.c_uint64, ctypes.c_uint32, vp]
     L.bs_gemm_create.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint64, ctypes.POINTER(vp)]
     L.bs_gemm_algo_count.argtypes = [vp]
     L.bs_gemm_run.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp]
@@ -155,6 +156,12 @@ def mix(reads, out0, out1, lds_reserve: int = 0, stream=None) -> None:
     arr = (ctypes.c_void_p * 10)(*[t.data_ptr() for t in reads])
     _check(lib().bs_mix(arr, out0.data_ptr(), out1.data_ptr(), out0.numel() * out0.element_size(),
                         lds_reserve, _sp(stream)), "bs_mix")
+
+
+def read(reads, sink, lds_reserve: int = 0, stream=None) -> None:
+    arr = (ctypes.c_void_p * 10)(*[t.data_ptr() for t in reads])
+    _check(lib().bs_read(arr, sink.data_ptr(), reads[0].numel() * reads[0].element_size(), lds_reserve,
+                         _sp(stream)), "bs_read")
 
 
 if __name__ == "__main__":
