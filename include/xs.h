@@ -322,8 +322,9 @@ typedef enum {
     XS_TUNE_REDUCE_LDS_RESERVE = 4, /* bytes of LDS reserved per reduce workgroup; the kernel uses no
                                        LDS, the reservation caps how many workgroups share a compute
                                        unit; -1 (default) = 16384: ten one-wave workgroups per compute unit
-                                       (28672, five, for 16 half-precision replicas with per-tensor
-                                       records or the unpack fused in) */
+                                       (20480 to 28672, eight to five, for most instances with the
+                                       unpack fused in and for 16 half-precision replicas with
+                                       per-tensor records) */
     XS_TUNE_REDUCE_MAX_WG = 5,      /* absolute cap on reduce workgroups, 0 = none */
     XS_TUNE_COPY_MAX_WG = 6,        /* absolute cap on pack/unpack workgroups, 0 = none */
     XS_TUNE_COPY_NT = 7,            /* pack/unpack: non-temporal accesses (0/1, default 1) */

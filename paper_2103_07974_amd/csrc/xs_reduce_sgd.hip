@@ -414,11 +414,22 @@ int launch_reduce_sgd(const Tuning &tn, const void *const *replicas, uint32_t W,
     // 20 loads per lane); more wavefronts than that only disorder the DRAM access stream,
     // fewer expose the latency of the kernel's prologue.  The LDS reservation (unused by the
     // kernel) is what caps the residency.
-    // The instances that look the row's tensor up (per-tensor records, unpack fused in) behave
-    // differently at W = 16 half-precision replicas (20 KiB in flight per wavefront): five per
-    // compute unit (28 KiB) is their optimum, +3 to +6 % over ten; at four they fall off again.
-    const bool looks_up = l.a.thp.rec != nullptr || l.a.param_ptrs != nullptr;
-    const int lds_auto = (half && W == 16 && looks_up) ? 28672 : 16384;
+    // The W-specialised instances that look the row's tensor up want fewer, not more, resident
+    // wavefronts than the plain kernel (measured on the VGG-16- and BERT-large-shaped sets, state
+    // in one pool; GB/s at the reservation below against 16 KiB):
+    //   unpack fused in, fp32:  W = 8: 6646 vs 6352 (5 per compute unit); W = 4: 6645 vs 6580 (8)
+    //   unpack fused in, half:  W = 16: 6447 vs 6202 (5); W = 8: 6407 vs 6311 (6); W = 4: 6496 vs
+    //                           6318 (6); W = 2: 6509 vs 6431 (8)
+    //   per-tensor records only, half, W = 16: 6573 vs 6293 (5); every other case is flat
+    const bool views = l.a.param_ptrs != nullptr, records = l.a.thp.rec != nullptr;
+    const bool specialised = !tn.reduce_small() && (W == 2 || W == 4 || W == 8 || W == 16);
+    int lds_auto = 16384;
+    if (specialised && views) {
+        if (!half) lds_auto = W >= 8 ? 28672 : (W == 4 ? 20480 : 16384);
+        else lds_auto = W >= 16 ? 28672 : (W >= 4 ? 24576 : 20480);
+    } else if (specialised && records && half && W == 16) {
+        lds_auto = 28672;
+    }
     l.lds_reserve = (unsigned)(tn.reduce_lds_reserve() < 0 ? lds_auto : tn.reduce_lds_reserve());
     const bool ntg = tn.nt_grads(), nts = tn.nt_state();
 
