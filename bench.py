@@ -845,7 +845,8 @@ def few_cu_sweep():
             t[getattr(xs, "TUNE_" + name)] = v
         return t
     shapes = [
-        ("default: one row per one-wave workgroup, 20 resident per CU", tuned()),
+        ("default: one row per one-wave workgroup, 13 resident per CU", tuned()),
+        ("20 resident per CU", tuned(GATHER_LDS_RESERVE=8192)),
         ("10 resident per CU", tuned(GATHER_LDS_RESERVE=16384)),
         ("as many as the registers allow", tuned(GATHER_LDS_RESERVE=0)),
         ("persistent grid, 10 one-wave workgroups per CU of the chip", tuned(REDUCE_WG_PER_CU=10, GATHER_LDS_RESERVE=0)),

@@ -328,7 +328,8 @@ typedef enum {
     XS_TUNE_REDUCE_MAX_WG = 5,      /* absolute cap on reduce workgroups, 0 = none */
     XS_TUNE_COPY_MAX_WG = 6,        /* absolute cap on pack/unpack workgroups, 0 = none */
     XS_TUNE_COPY_NT = 7,            /* pack/unpack: non-temporal accesses (0/1, default 1) */
-    XS_TUNE_GATHER_LDS_RESERVE = 8, /* as 4 for the gathering form; -1 = 8192 fp32, 16384 half */
+    XS_TUNE_GATHER_LDS_RESERVE = 8, /* as 4 for the gathering form; -1 = 8192 to 12288 fp32, 10240 to
+                                       16384 half, by W */
     XS_TUNE_COPY_LDS_RESERVE = 9,   /* pack/unpack: bytes of LDS reserved per workgroup (the kernel uses
                                        none; caps the workgroups per compute unit); -1 (default) = 0 */
     XS_TUNE_REDUCE_WAVES_PER_WG = 10, /* gathering form and the generic-W bucket-form kernel (any W outside

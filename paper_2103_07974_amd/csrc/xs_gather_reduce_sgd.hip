@@ -11,10 +11,10 @@
 // Work unit: one row of 1 KiB of gradient data per replica = one 16-byte vector per lane of
 // a one-wavefront workgroup, dispatched in bucket order (the launch shape that measured
 // fastest for the bucket form).  The plan's row table gives the tensor that holds the row's
-// first element; lanes step forward from there (rows that cross tensor boundaries are the
-// exception: 64-element layers are the smallest in the workloads).  When the whole wavefront
-// sits in one tensor, the W tensor addresses come through scalar loads; otherwise each lane
-// fetches its own.  A vector that lies wholly inside a tensor's valid range takes the vector
+// first element.  When the row is a complete row of valid elements of that tensor (the rule:
+// 64-element layers are the smallest in the workloads) that is decided from three scalar
+// look-ups and the W tensor addresses come through scalar loads too; otherwise lanes step
+// forward from the row's first tensor and each fetches its own.  A vector that lies wholly inside a tensor's valid range takes the vector
 // path (element-aligned 16-byte loads from the tensors); vectors that touch padding or
 // straddle tensors (tight layouts) go element by element, with padding contributing +0
 // exactly as a packed bucket would.
@@ -143,6 +143,22 @@ __global__ __launch_bounds__(kMaxReduceThreads) void gather_reduce_sgd_kernel(Ga
     for (uint64_t row = (uint64_t)blockIdx.x * waves + wave; row < a.n_rows; row += (uint64_t)gridDim.x * waves) {
         const uint64_t j = row * ROW + (uint64_t)lane * VEC;           // lane's first bucket element
         if (j >= a.n_bucket) continue;
+        {
+            // The rule: a complete row of valid elements of one tensor.  Decided from three
+            // wave-uniform look-ups through the scalar cache (the tables are not written while
+            // the kernel runs); the tensor addresses follow the same way.
+            typedef const __attribute__((address_space(4))) uint32_t cu32;
+            typedef const __attribute__((address_space(4))) uint64_t cu64;
+            const uint32_t ts = (uint32_t)__builtin_amdgcn_readfirstlane((int)((cu32 *)a.tb.row_first)[row]);
+            const uint64_t off = ((cu64 *)a.tb.offsets)[ts];
+            const uint64_t num = ((cu64 *)a.tb.numel)[ts];
+            const uint64_t row_end = (row + 1) * ROW;
+            if (off + num >= row_end && row_end <= a.n_bucket) {
+                vector_path<W, GT, DETECT, VIEWS, PT, Grad<GT>::HALF>(a, ts, j, j - off, bad);
+                continue;
+            }
+        }
+        // rows that cross tensors, touch padding or end the bucket: per-lane look-ups
         const uint32_t t_row = a.tb.row_first[row];
         uint32_t t = t_row;
         while (t + 1 < a.n_tensors && a.tb.offsets[t + 1] <= j) ++t;
@@ -278,9 +294,16 @@ int launch_gather_reduce_sgd(const Tuning &tn, const xs_plan *plan, const void *
         blocks = (uint64_t)tn.reduce_max_wg();
     if (blocks > 0x7fffffffull) blocks = 0x7fffffffull;
     const dim3 grid((unsigned)blocks), block((unsigned)(waves * kWave));
-    // the address look-ups in front of the loads want about twice the residency of the
-    // bucket form: 20 one-wave workgroups per compute unit for fp32, 10 for half precision
-    const int lds_auto = half ? 16384 : 8192;
+    // The look-ups in front of the loads want more resident wavefronts than the bucket form,
+    // the fewer the more bytes a wavefront has in flight.  Measured optimum (one-wave
+    // workgroups per compute unit, VGG-16- and BERT-large-shaped sets):
+    //   fp32: W = 8: 13 (12 KiB), W = 4: 16 (10 KiB), W = 2: 20 (8 KiB)
+    //   half: W = 16: 8-10 (16-20 KiB), W = 8: 13, W = 4 and 2: 16
+    int lds_auto = half ? 16384 : 8192;
+    if (W == 2 || W == 4 || W == 8 || W == 16) {
+        if (!half) lds_auto = W >= 8 ? 12288 : (W == 4 ? 10240 : 8192);
+        else lds_auto = W >= 16 ? 16384 : (W == 8 ? 12288 : 10240);
+    }
     const unsigned lds = (unsigned)(tn.gather_lds_reserve() < 0 ? lds_auto : tn.gather_lds_reserve());
     const bool views = param_ptrs != nullptr;
 
